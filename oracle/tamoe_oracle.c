@@ -1,0 +1,413 @@
+/*
+ * CPU oracle for the one-device TA-MoE hot path.  TEST INFRASTRUCTURE ONLY.
+ *
+ * A plain, slow, double-precision restatement of what the paper
+ * "TA-MoE: Topology-Aware Large Scale Mixture-of-Expert Training" defines for
+ * one device i of an expert-parallel MoE layer.  Scalar loops, no BLAS, no
+ * blocking, no fusion.  It exists so that the HIP library can be checked
+ * against something independent: it shares no source, header, table or helper
+ * with the HIP path and nothing in the product may call it.  Only the tests,
+ * the smoke check and the benchmark's "cpu_baseline" leg use it.
+ *
+ * Notation (Section 3.1 "MoE Model Structure"): N experts, P devices,
+ * E = N/P experts per device (device j holds experts jE .. (j+1)E-1), S tokens
+ * on this device, k experts selected per token, hidden size d.  c[e] is the
+ * number of (token, choice) pairs of this device that selected expert e,
+ * G(x) the softmax gate vector, m[e] the mean of G(x)[e] over the S tokens.
+ *
+ * The only parallelism is an OpenMP "parallel for" over tokens on loops whose
+ * iterations are independent (used by the benchmark's all-cores timing); the
+ * arithmetic of each iteration is unchanged by it.
+ *
+ * Every function below is pinned by tests/test_oracle_*.py against closed
+ * forms, invariants, brute force, library routines and the worked numbers of
+ * the paper's Table 1.  Not pinned ("parity unpinned"): none of the exported
+ * functions; the paper's softmax-type Norm, asymmetric-tree merge and global
+ * capacity are not implemented here at all.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+#define ORC_F32 0
+#define ORC_BF16 1
+
+static int g_threads = 1;
+
+void orc_set_threads(int n) { g_threads = n < 1 ? 1 : n; }
+
+int orc_max_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_num_procs();
+#else
+    return 1;
+#endif
+}
+
+/* ---- storage types ------------------------------------------------------ */
+
+static size_t elem_size(int dtype) { return dtype == ORC_F32 ? 4u : 2u; }
+
+/* exact value of element i of a float32 / bfloat16 buffer */
+static double load_elem(const void *buf, int dtype, int64_t i)
+{
+    if (dtype == ORC_F32)
+        return (double)((const float *)buf)[i];
+    uint32_t bits = (uint32_t)((const uint16_t *)buf)[i] << 16;
+    float f;
+    memcpy(&f, &bits, 4);
+    return (double)f;
+}
+
+/* nearest bfloat16 (8 significand bits), ties to even, straight from double:
+ * no intermediate float rounding */
+static uint16_t round_to_bf16(double v)
+{
+    if (v == 0.0 || isnan(v)) {
+        uint16_t z = (uint16_t)(signbit(v) ? 0x8000u : 0u);
+        return isnan(v) ? (uint16_t)0x7FC0u : z;
+    }
+    if (isinf(v))
+        return (uint16_t)(v > 0 ? 0x7F80u : 0xFF80u);
+    int ex;
+    (void)frexp(fabs(v), &ex); /* |v| = f * 2^ex, f in [0.5, 1) => |v| in [2^(ex-1), 2^ex) */
+    int e = ex - 1;            /* floor(log2 |v|) */
+    if (e < -126)
+        e = -126;              /* subnormal range shares the spacing of the smallest normal */
+    double ulp = ldexp(1.0, e - 7);
+    double q = nearbyint(v / ulp); /* default rounding mode: to nearest, ties to even */
+    double r = q * ulp;            /* representable in bfloat16 unless it overflowed */
+    float f = (float)r;            /* exact */
+    if (isinf(f) || fabs(r) >= ldexp(1.0, 128))
+        return (uint16_t)(v > 0 ? 0x7F80u : 0xFF80u);
+    uint32_t bits;
+    memcpy(&bits, &f, 4);
+    return (uint16_t)(bits >> 16);
+}
+
+static void store_elem(void *buf, int dtype, int64_t i, double v)
+{
+    if (dtype == ORC_F32)
+        ((float *)buf)[i] = (float)v;
+    else
+        ((uint16_t *)buf)[i] = round_to_bf16(v);
+}
+
+/* exported so the rounding itself can be pinned by a test */
+uint16_t orc_round_to_bf16(double v) { return round_to_bf16(v); }
+
+/* ---- setup: communication model, target pattern, penalty ----------------- */
+
+/*
+ * Per-level smoothing of a profiled inverse-bandwidth table (Section 4.2
+ * "Model Optimization", the alpha_l / beta_l definition and the hierarchical
+ * matrix that follows it).  level[i*P+j] labels the tree level of the pair
+ * (i, j).  beta_l is the mean of beta_ij over the pairs i < j on level l (the
+ * paper's printed pair count only equals the real one on the deepest level;
+ * the mean over the actual pairs is what "eliminate the noise of profiling"
+ * needs).  A level that occurs only on the diagonal (self transfers) has no
+ * pair i < j; its value is the mean of those diagonal entries.
+ * beta_hat_ij = beta_{level(i,j)}.  Returns 0, or 1 on a bad level label.
+ */
+int orc_smooth_beta(const double *beta, const int32_t *level, int P, double *beta_hat)
+{
+    int n_levels = 0;
+    for (int q = 0; q < P * P; ++q) {
+        if (level[q] < 0)
+            return 1;
+        if (level[q] + 1 > n_levels)
+            n_levels = level[q] + 1;
+    }
+    double *sum = (double *)calloc((size_t)n_levels, sizeof(double));
+    double *cnt = (double *)calloc((size_t)n_levels, sizeof(double));
+    double *dsum = (double *)calloc((size_t)n_levels, sizeof(double));
+    double *dcnt = (double *)calloc((size_t)n_levels, sizeof(double));
+    for (int i = 0; i < P; ++i) {
+        for (int j = i + 1; j < P; ++j) {
+            int l = level[i * P + j];
+            sum[l] += beta[i * P + j];
+            cnt[l] += 1.0;
+        }
+        int l = level[i * P + i];
+        dsum[l] += beta[i * P + i];
+        dcnt[l] += 1.0;
+    }
+    for (int i = 0; i < P; ++i) {
+        for (int j = 0; j < P; ++j) {
+            int l = level[i * P + j];
+            beta_hat[i * P + j] = cnt[l] > 0.0 ? sum[l] / cnt[l] : dsum[l] / dcnt[l];
+        }
+    }
+    free(sum); free(cnt); free(dsum); free(dcnt);
+    return 0;
+}
+
+/*
+ * Target dispatch pattern of device `rank` (Section 4.2, the closed-form
+ * solution of the min-max problem after the latency term is dropped):
+ *   c_hat[e] = k*S / ( E * (sum_j 1/beta_hat[rank][j]) * beta_hat[rank][floor(e/E)] )
+ * The sum runs over all P devices, j = rank included.
+ */
+void orc_target_pattern(const double *beta_hat, int P, int N, int rank, int k, int64_t S,
+                        double *c_hat)
+{
+    int E = N / P;
+    const double *row = beta_hat + (size_t)rank * P;
+    double Z = 0.0;
+    for (int j = 0; j < P; ++j)
+        Z += 1.0 / row[j];
+    for (int e = 0; e < N; ++e)
+        c_hat[e] = (double)k * (double)S / ((double)E * Z * row[e / E]);
+}
+
+/* Penalty weights (Section 4.3 "Routing Strategy"): p = Norm(1 / c_hat) with Norm = divide
+ * by the sum, so that sum_e p[e] = 1 (the reading under which the N*P factor of the loss
+ * keeps the magnitude of the loss: homogeneous network => N * p[e] = 1). */
+void orc_penalty(const double *c_hat, int N, double *p)
+{
+    double tot = 0.0;
+    for (int e = 0; e < N; ++e)
+        tot += 1.0 / c_hat[e];
+    for (int e = 0; e < N; ++e)
+        p[e] = (1.0 / c_hat[e]) / tot;
+}
+
+/*
+ * Local capacity per expert (Section 3.1, last paragraph, and Section 4.3,
+ * the paragraph on DeepSpeed-MoE): mode 0 is the uniform capacity at the
+ * load-balanced target, ceil(cf * k*S/N); mode 1 makes it proportional to
+ * the target pattern, ceil(cf * c_hat[e]).  A product that is an integer up
+ * to 1e-9 is taken as that integer.
+ */
+void orc_capacity(const double *c_hat, int N, int k, int64_t S, double cf, int mode, int32_t *cap)
+{
+    for (int e = 0; e < N; ++e) {
+        double v = mode == 0 ? cf * (double)k * (double)S / (double)N : cf * c_hat[e];
+        cap[e] = (int32_t)ceil(v - 1e-9);
+    }
+}
+
+/*
+ * Value of the exchange objective (Section 4.1 "Communication Model"): the slowest of the
+ * P*P peer deliveries, max_{i,j} ( alpha_ij + beta_ij * sum_{e on device j} c[i][e] * bytes ),
+ * bytes = d*b per token row.  alpha may be NULL (zero latency).  c is [P][N].
+ */
+double orc_exchange_cost(const double *alpha, const double *beta, const double *c, int P, int N,
+                         double bytes_per_row)
+{
+    int E = N / P;
+    double worst = -INFINITY;
+    for (int i = 0; i < P; ++i) {
+        for (int j = 0; j < P; ++j) {
+            double rows = 0.0;
+            for (int e = E * j; e <= E * (j + 1) - 1; ++e)
+                rows += c[(size_t)i * N + e];
+            double t = (alpha ? alpha[i * P + j] : 0.0) + beta[i * P + j] * rows * bytes_per_row;
+            if (t > worst)
+                worst = t;
+        }
+    }
+    return worst;
+}
+
+/* ---- gate: scores, softmax, top-k ---------------------------------------- */
+
+/* Gate scores (Section 3.1, first paragraph): logits[t][e] = sum_q x[t][q] * W[e][q]. */
+void orc_logits(const void *x, const void *w, int dtype, int64_t S, int d, int N, double *logits)
+{
+#pragma omp parallel for num_threads(g_threads) schedule(static)
+    for (int64_t t = 0; t < S; ++t) {
+        for (int e = 0; e < N; ++e) {
+            double acc = 0.0;
+            for (int q = 0; q < d; ++q)
+                acc += load_elem(x, dtype, t * d + q) * load_elem(w, dtype, (int64_t)e * d + q);
+            logits[t * N + e] = acc;
+        }
+    }
+}
+
+/* Softmax over the N experts of each token (Section 3.1): the gate vector G(x). */
+void orc_softmax(const double *logits, int64_t S, int N, double *G)
+{
+#pragma omp parallel for num_threads(g_threads) schedule(static)
+    for (int64_t t = 0; t < S; ++t) {
+        const double *l = logits + t * N;
+        double mx = l[0];
+        for (int e = 1; e < N; ++e)
+            if (l[e] > mx)
+                mx = l[e];
+        double den = 0.0;
+        for (int e = 0; e < N; ++e)
+            den += exp(l[e] - mx);
+        for (int e = 0; e < N; ++e)
+            G[t * N + e] = exp(l[e] - mx) / den;
+    }
+}
+
+/*
+ * Top-k selection (Section 3.1: only the experts with the top k scores process the sample).
+ * Selection is on the scores; equal scores go to the lower expert index; the k choices are
+ * listed best first.  The combine weight of a choice is its softmax value, not renormalised.
+ */
+void orc_topk(const double *logits, const double *G, int64_t S, int N, int k,
+              int32_t *idx, double *wgt)
+{
+#pragma omp parallel for num_threads(g_threads) schedule(static)
+    for (int64_t t = 0; t < S; ++t) {
+        const double *l = logits + t * N;
+        for (int j = 0; j < k; ++j) {
+            int best = -1;
+            for (int e = 0; e < N; ++e) {
+                int taken = 0;
+                for (int jj = 0; jj < j; ++jj)
+                    if (idx[t * k + jj] == e)
+                        taken = 1;
+                if (taken)
+                    continue;
+                if (best < 0 || l[e] > l[best])
+                    best = e; /* strict '>' keeps the lowest index among equals */
+            }
+            idx[t * k + j] = best;
+            wgt[t * k + j] = G[t * N + best];
+        }
+    }
+}
+
+/*
+ * Load statistics of this device before any capacity pruning (Section 3.1 and the merged
+ * per-device delivery of Section 4.1): c_expert[e] = number of (t, j) with idx[t][j] = e,
+ * c_device[j] = sum of c_expert over the experts of device j, m[e] = (1/S) sum_t G[t][e].
+ */
+void orc_counts(const int32_t *idx, const double *G, int64_t S, int N, int P, int k,
+                int32_t *c_expert, int32_t *c_device, double *m)
+{
+    int E = N / P;
+    for (int e = 0; e < N; ++e)
+        c_expert[e] = 0;
+    for (int64_t t = 0; t < S; ++t)
+        for (int j = 0; j < k; ++j)
+            c_expert[idx[t * k + j]] += 1;
+    for (int j = 0; j < P; ++j) {
+        c_device[j] = 0;
+        for (int e = E * j; e <= E * (j + 1) - 1; ++e)
+            c_device[j] += c_expert[e];
+    }
+    for (int e = 0; e < N; ++e) {
+        double s = 0.0;
+        for (int64_t t = 0; t < S; ++t)
+            s += G[t * N + e];
+        m[e] = s / (double)S;
+    }
+}
+
+/* Load-balance loss (Section 3.1): l_aux = sum_e m[e] * (c[e] / S). */
+double orc_l_aux(const double *m, const int32_t *c, int N, int64_t S)
+{
+    double l = 0.0;
+    for (int e = 0; e < N; ++e)
+        l += m[e] * ((double)c[e] / (double)S);
+    return l;
+}
+
+/* Topology-aware loss (Section 4.3): l_topo = N*P * sum_e p[e] * m[e] * c[e] / S. */
+double orc_l_topo(const double *p, const double *m, const int32_t *c, int N, int P, int64_t S)
+{
+    double l = 0.0;
+    for (int e = 0; e < N; ++e)
+        l += p[e] * m[e] * (double)c[e] / (double)S;
+    return (double)N * (double)P * l;
+}
+
+/* ---- capacity-limited dispatch and combine ------------------------------- */
+
+/*
+ * Capacity pruning and send-buffer positions (Section 3.1 local capacity c_ie <= C_ie;
+ * Section 4.1 chunks for one device merged into one delivery; Section 4.3 variable sizes
+ * instead of zero padding).  The (token, choice) pairs are visited choice-major: every first
+ * choice in token order, then every second choice, ...  The pair's position among the pairs of
+ * its expert is pos; it is kept iff pos < cap[e].  kept[e] = min(c[e], cap[e]); the send buffer
+ * lists the kept rows expert by expert (hence device by device), off[e] = sum of kept[e'] for
+ * e' < e, slot = off[e] + pos, or -1 for a dropped pair.  send_count_dev[j] is the number of
+ * rows bound for device j.  Returns K = off[N], the number of rows in the send buffer.
+ */
+int64_t orc_slots(const int32_t *idx, const int32_t *cap, int64_t S, int N, int P, int k,
+                  int32_t *slot, int32_t *kept, int32_t *off, int32_t *send_count_dev)
+{
+    int E = N / P;
+    int32_t *counter = (int32_t *)calloc((size_t)N, sizeof(int32_t));
+    int32_t *pos = (int32_t *)malloc((size_t)S * k * sizeof(int32_t));
+    for (int j = 0; j < k; ++j) {
+        for (int64_t t = 0; t < S; ++t) {
+            int e = idx[t * k + j];
+            pos[t * k + j] = counter[e];
+            counter[e] += 1;
+        }
+    }
+    for (int e = 0; e < N; ++e)
+        kept[e] = counter[e] < cap[e] ? counter[e] : cap[e];
+    off[0] = 0;
+    for (int e = 0; e < N; ++e)
+        off[e + 1] = off[e] + kept[e];
+    for (int64_t t = 0; t < S; ++t) {
+        for (int j = 0; j < k; ++j) {
+            int e = idx[t * k + j];
+            slot[t * k + j] = pos[t * k + j] < cap[e] ? off[e] + pos[t * k + j] : -1;
+        }
+    }
+    for (int j = 0; j < P; ++j) {
+        send_count_dev[j] = 0;
+        for (int e = E * j; e <= E * (j + 1) - 1; ++e)
+            send_count_dev[j] += kept[e];
+    }
+    free(counter);
+    free(pos);
+    return (int64_t)off[N];
+}
+
+/* Scatter (Section 3.1: dispatched data of shape [k*S, d], [c_ie, d] per expert): a bit copy
+ * send[slot[t][j]][:] = x[t][:] for every kept pair. */
+void orc_scatter(const void *x, int dtype, const int32_t *slot, int64_t S, int d, int k, void *send)
+{
+    size_t row = (size_t)d * elem_size(dtype);
+#pragma omp parallel for num_threads(g_threads) schedule(static)
+    for (int64_t t = 0; t < S; ++t) {
+        for (int j = 0; j < k; ++j) {
+            int32_t s = slot[t * k + j];
+            if (s >= 0)
+                memcpy((char *)send + (size_t)s * row, (const char *)x + (size_t)t * row, row);
+        }
+    }
+}
+
+/*
+ * Combine (Section 3.1: the layer output y aggregates the computed results): recv holds the
+ * expert outputs in the row order of the send buffer;
+ *   y[t][:] = sum over kept choices j (ascending) of wgt[t][j] * recv[slot[t][j]][:],
+ * a zero row if every choice of the token was dropped.  y_exact (may be NULL) receives the
+ * double result, y (may be NULL) the result rounded once to the storage type.
+ */
+void orc_combine(const void *recv, int dtype, const int32_t *slot, const double *wgt,
+                 int64_t S, int d, int k, double *y_exact, void *y)
+{
+#pragma omp parallel for num_threads(g_threads) schedule(static)
+    for (int64_t t = 0; t < S; ++t) {
+        for (int q = 0; q < d; ++q) {
+            double acc = 0.0;
+            for (int j = 0; j < k; ++j) {
+                int32_t s = slot[t * k + j];
+                if (s >= 0)
+                    acc += wgt[t * k + j] * load_elem(recv, dtype, (int64_t)s * d + q);
+            }
+            if (y_exact)
+                y_exact[t * d + q] = acc;
+            if (y)
+                store_elem(y, dtype, t * d + q, acc);
+        }
+    }
+}
