@@ -1,0 +1,189 @@
+/*
+ * tamoe.h - C ABI of the one-device hot path of TA-MoE
+ * ("TA-MoE: Topology-Aware Large Scale Mixture-of-Expert Training", NeurIPS 2022)
+ * for AMD MI355X (gfx950).
+ *
+ * The path, for one device (rank) i of an expert-parallel MoE layer, in the paper's
+ * notation (Section 3.1): N experts, P devices, E = N/P experts per device (device j holds
+ * experts jE .. (j+1)E-1), S tokens on this device, k experts selected per token, hidden
+ * size d:
+ *
+ *   tamoe_topo_pattern  host, once per topology: target dispatch pattern, penalty, capacity
+ *   tamoe_gate          scores x W^T, softmax, top-k, load statistics
+ *   tamoe_aux_loss      topology-aware auxiliary loss l_topo (or the plain l_aux)
+ *   tamoe_dispatch      capacity-limited slot assignment + scatter into the send buffer
+ *   tamoe_combine       weighted gather of the returned rows into y
+ *
+ * The global exchange, the experts and the return exchange sit between tamoe_dispatch and
+ * tamoe_combine and are not part of this library.
+ *
+ * Conventions
+ *  - Every matrix is row-major and dense.  Counts, indices and slots are int32_t.
+ *  - "device" pointers are HIP device memory of the current device; "host" pointers are
+ *    ordinary host memory.  The caller owns every buffer; the library allocates nothing and
+ *    keeps no state between calls.  Scratch comes from the caller's workspace `ws` (device
+ *    memory, 256-byte aligned, at least tamoe_workspace_bytes() bytes).  Its content is
+ *    garbage on entry and on exit; two calls that share a workspace must be ordered on one
+ *    stream.
+ *  - Device functions only enqueue work on `stream` (a hipStream_t passed as void*; NULL is
+ *    the default stream).  They never synchronise and are deterministic: same inputs, same
+ *    bits.
+ *  - dtype: TAMOE_F32 (float) or TAMOE_BF16 (bfloat16 bit patterns, 2 bytes per element).
+ *    A token row must be a multiple of 16 bytes (d % 4 == 0 for F32, d % 8 == 0 for BF16) and
+ *    x, W, send, recv, y must be 16-byte aligned.
+ *  - Limits: 1 <= N <= TAMOE_MAX_EXPERTS, 1 <= k <= min(N, TAMOE_MAX_K), N % P == 0,
+ *    S * k < 2^31.  S = 0 is accepted by every device function except tamoe_aux_loss.
+ *  - Inputs must be finite.  NaN scores give unspecified (but in-range or -1) selections.
+ *  - Every function returns a tamoe_status.  On failure nothing has been enqueued and
+ *    tamoe_last_error() describes the reason (thread-local, valid until the next call).
+ */
+#ifndef TAMOE_H
+#define TAMOE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define TAMOE_VERSION 1
+
+#define TAMOE_MAX_EXPERTS 128
+#define TAMOE_MAX_K 8
+
+typedef enum tamoe_status {
+    TAMOE_OK = 0,
+    TAMOE_INVALID_ARG = 1,        /* null pointer, non-positive size, k > N, N % P != 0, rank
+                                     outside [0,P), misaligned pointer, bad beta, bad level */
+    TAMOE_UNSUPPORTED = 2,        /* dtype, N or k beyond the limits, row not a multiple of 16 B */
+    TAMOE_WORKSPACE_TOO_SMALL = 3,
+    TAMOE_HIP_ERROR = 4           /* a kernel launch was rejected by the HIP runtime */
+} tamoe_status;
+
+enum { TAMOE_F32 = 0, TAMOE_BF16 = 1 };
+enum { TAMOE_CAP_UNIFORM = 0, TAMOE_CAP_PROPORTIONAL = 1 };
+
+int tamoe_version(void);
+
+/* Message of the last failure on the calling thread ("" if none). */
+const char* tamoe_last_error(void);
+
+/*
+ * Setup, host only (all pointers host).  Section 4.2 "Model Optimization" and Section 4.3
+ * "Routing Strategy" of the paper:
+ *   1. if `level` is not NULL, smooth the profiled table per tree level: beta_l is the mean of
+ *      beta[i][j] over the pairs i < j with level[i][j] == l (a label that occurs only on the
+ *      diagonal takes the mean of those diagonal entries), beta_hat[i][j] = beta_{level[i][j]}
+ *      (the hierarchical matrix); with level == NULL, beta is used as it is;
+ *   2. target pattern of device `rank` (closed-form solution of the min-max exchange problem,
+ *      latency dropped):
+ *        c_hat[e] = k*S / ( E * (sum_{j=0..P-1} 1/beta_hat[rank][j]) * beta_hat[rank][e/E] );
+ *   3. penalty[e] = (1/c_hat[e]) / sum_e' (1/c_hat[e'])          (p_i = Norm(1/c_hat_i));
+ *   4. cap[e] = ceil(capacity_factor * k*S/N)      for cap_mode TAMOE_CAP_UNIFORM,
+ *               ceil(capacity_factor * c_hat[e])   for cap_mode TAMOE_CAP_PROPORTIONAL
+ *      (local capacity C_ie, Section 3.1 / Section 4.3; a product within 1e-9 of an integer
+ *      counts as that integer).
+ * beta  [P*P] inverse bandwidth of every device pair, diagonal included, all > 0 and finite.
+ * level [P*P] non-negative tree-level label of every pair, or NULL.
+ * Outputs (each may be NULL to skip it): c_hat [N] double, penalty [N] float, cap [N] int32.
+ */
+int tamoe_topo_pattern(const double* beta, const int32_t* level, int P, int N, int rank, int k,
+                       int64_t S, double capacity_factor, int cap_mode,
+                       double* c_hat, float* penalty, int32_t* cap);
+
+/* Bytes of device workspace that any of the device functions below needs for this shape. */
+size_t tamoe_workspace_bytes(int64_t S, int d, int N, int P, int k, int dtype);
+
+/*
+ * Gate (Section 3.1: gate network G, softmax, top-k; load statistics of Section 3.1 / 4.1).
+ *   logits[t][e]  = sum_q x[t][q] * W[e][q]             (fp32 accumulation)
+ *   G[t][:]       = softmax over the N experts of logits[t][:]
+ *   topk_idx[t][j], j = 0..k-1: the k experts with the highest logits, best first, equal
+ *                   logits to the lower expert index;  topk_w[t][j] = G[t][topk_idx[t][j]]
+ *                   (not renormalised over the k choices)
+ *   c_expert[e]   = number of (t, j) with topk_idx[t][j] == e        (before any capacity)
+ *   c_device[j]   = sum of c_expert over the experts of device j
+ *   m[e]          = (1/S) * sum_t G[t][e]                             (0 if S == 0)
+ * x [S,d], w [N,d]: device, `dtype`.   logits [S,N] float, device, may be NULL.
+ * topk_idx [S,k] int32, topk_w [S,k] float, m [N] float, c_expert [N] int32,
+ * c_device [P] int32: device outputs.  The selection is taken on exactly the fp32 logits that
+ * are written to `logits`.
+ */
+int tamoe_gate(const void* x, const void* w, int dtype, int64_t S, int d, int N, int P, int k,
+               float* logits, int32_t* topk_idx, float* topk_w, float* m,
+               int32_t* c_expert, int32_t* c_device,
+               void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * The gate's selection stage on given scores: everything tamoe_gate computes after the matrix
+ * product, from logits [S,N] float (device).  Same outputs, same arithmetic.
+ */
+int tamoe_select(const float* logits, int64_t S, int N, int P, int k,
+                 int32_t* topk_idx, float* topk_w, float* m,
+                 int32_t* c_expert, int32_t* c_device,
+                 void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Auxiliary loss (Section 4.3, the topology loss; Section 3.1, the load-balance loss).
+ *   penalty != NULL:  loss = N*P * sum_e penalty[e] * m[e] * c_expert[e] / S      (l_topo)
+ *   penalty == NULL:  loss =       sum_e              m[e] * c_expert[e] / S      (l_aux)
+ * m [N] float, c_expert [N] int32, penalty [N] float, loss [1] float: device.  S > 0.
+ */
+int tamoe_aux_loss(const float* m, const int32_t* c_expert, const float* penalty,
+                   int N, int P, int64_t S, float* loss, void* stream);
+
+/*
+ * Capacity-limited dispatch (Section 3.1: dispatched data [k*S, d], [c_ie, d] per expert, local
+ * capacity c_ie <= C_ie; Section 4.1: chunks for one device merged into one delivery; Section
+ * 4.3: variable chunk sizes instead of zero padding).
+ * Pairs (t, j) are ranked choice-major: all first choices in token order, then all second
+ * choices, ...  pos(t,j) = number of earlier pairs with the same expert e = topk_idx[t][j].
+ * The pair is kept iff pos < cap[e].
+ *   kept_expert[e]    = min(c_expert[e], cap[e])
+ *   expert_offset[e]  = sum_{e' < e} kept_expert[e'],  expert_offset[N] = K (rows in `send`)
+ *   slot[t][j]        = expert_offset[e] + pos  if kept, else -1
+ *   send_count_dev[j] = sum of kept_expert over the experts of device j  (rows bound for j)
+ *   send[slot[t][j]][:] = x[t][:]   bit copy, for every kept pair
+ * so `send` lists rows expert by expert, hence destination device by destination device.
+ * An index outside [0, N) in topk_idx is treated as a dropped pair (slot -1, not counted).
+ * x [S,d] `dtype`, topk_idx [S,k], cap [N] (>= 0): device inputs.  send: device, room for k*S
+ * rows of d elements; only the first K rows are written.  slot [S,k], kept_expert [N],
+ * expert_offset [N+1], send_count_dev [P]: device outputs.
+ */
+int tamoe_dispatch(const void* x, const int32_t* topk_idx, const int32_t* cap, int dtype,
+                   int64_t S, int d, int N, int P, int k,
+                   void* send, int32_t* slot, int32_t* kept_expert, int32_t* expert_offset,
+                   int32_t* send_count_dev,
+                   void* ws, size_t ws_bytes, void* stream);
+
+/*
+ * Weighted combine (Section 3.1: the output y of the layer aggregates the computed results).
+ * recv holds the expert outputs in the row order of the send buffer.
+ *   y[t][:] = sum over j = 0..k-1 with slot[t][j] >= 0 of topk_w[t][j] * recv[slot[t][j]][:]
+ * accumulated in fp32 in ascending j and rounded once to `dtype`; a token whose choices were
+ * all dropped gets a zero row.  A slot >= K_rows is ignored like a dropped pair.
+ * recv [K_rows,d] `dtype`, slot [S,k], topk_w [S,k] float: device inputs; y [S,d]: device out.
+ */
+int tamoe_combine(const void* recv, int64_t K_rows, const int32_t* slot, const float* topk_w,
+                  int dtype, int64_t S, int d, int k, void* y, void* stream);
+
+/*
+ * Kernel timing aid for benchmarks (not a step of the path; off unless started).
+ * tamoe_trace_start creates 2*max_launches HIP events on the current device; from then on every
+ * kernel the device functions above enqueue is bracketed by a pair of events on its stream,
+ * until max_launches kernels have been recorded or tamoe_trace_stop is called.
+ * tamoe_trace_stop waits for the recorded events and returns the number of records (>= 0), or
+ * a negative tamoe_status.  tamoe_trace_get copies record i: the kernel's name (truncated to
+ * name_len-1 characters) and its duration in milliseconds.  tamoe_trace_clear destroys the
+ * events.  One trace at a time, process-wide; not thread-safe.  All pointers host.
+ */
+int tamoe_trace_start(int max_launches);
+int tamoe_trace_stop(void);
+int tamoe_trace_get(int i, char* name, size_t name_len, float* ms);
+int tamoe_trace_clear(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TAMOE_H */

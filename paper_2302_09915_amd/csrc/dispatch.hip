@@ -1,0 +1,227 @@
+// tamoe_dispatch: capacity-limited slot assignment by prefix scans, and the row scatter into the
+// destination-grouped send buffer (paper Section 3.1: dispatched data [k*S, d], local capacity;
+// Section 4.1: one merged delivery per destination device; Section 4.3: variable chunk sizes).
+//
+// Three launches, no atomics on positions, so the result is the same on every run:
+//   1. dispatch_count_kernel   pairs per (choice j, count tile of 1024 tokens, expert)
+//   2. dispatch_scan_kernel    exclusive prefix of those counts in priority order (choice-major,
+//                              then token order), kept = min(count, cap), expert offsets,
+//                              rows per destination device
+//   3. dispatch_scatter_kernel one workgroup per row tile (4..64 tokens): recount the pairs of
+//                              the count tile that precede the row tile, rank the tile's own
+//                              pairs, write slot[], then stream the rows: each 16-byte chunk
+//                              of a kept token is read once and stored to each of its slots.
+//
+// The scatter is bound by HBM: it reads d*b bytes per token with a kept choice and writes d*b
+// bytes per kept pair.  Chunks of a tile are laid out flat over the workgroup's threads, so a
+// wavefront always touches 1 KiB of consecutive bytes of a row, whatever d is.
+#include "internal.h"
+
+namespace tamoe {
+
+constexpr int kThreads = 256;
+constexpr int kMaxRowTile = 64;
+
+__global__ __launch_bounds__(kThreads) void dispatch_count_kernel(
+    const int32_t* __restrict__ idx, int64_t S, int N, int k, int n_ct, int32_t* __restrict__ tile_count) {
+    __shared__ int32_t hist[TAMOE_MAX_K * TAMOE_MAX_EXPERTS];
+    const int ct = blockIdx.x;
+    for (int q = threadIdx.x; q < k * N; q += kThreads) hist[q] = 0;
+    __syncthreads();
+    const int64_t p_begin = (int64_t)ct * kCountTile * k;
+    int64_t p_end = p_begin + (int64_t)kCountTile * k;
+    if (p_end > S * k) p_end = S * k;
+    for (int64_t p = p_begin + threadIdx.x; p < p_end; p += kThreads) {
+        const int e = idx[p];
+        const int j = (int)(p % k);
+        if (e >= 0 && e < N) atomicAdd(&hist[j * N + e], 1);
+    }
+    __syncthreads();
+    for (int q = threadIdx.x; q < k * N; q += kThreads) {
+        const int j = q / N, e = q - j * N;
+        tile_count[((size_t)j * n_ct + ct) * N + e] = hist[q];
+    }
+}
+
+// One workgroup of 1024 threads: thread (part, e) owns a contiguous eighth of expert e's
+// entries.  Entry q = j * n_ct + ct; ascending q is the priority order.
+constexpr int kScanThreads = 1024;
+constexpr int kScanParts = kScanThreads / TAMOE_MAX_EXPERTS;
+
+__global__ __launch_bounds__(kScanThreads) void dispatch_scan_kernel(
+    int32_t* __restrict__ tile_count, const int32_t* __restrict__ cap, int N, int P, int n_entries,
+    int32_t* __restrict__ kept_expert, int32_t* __restrict__ expert_offset,
+    int32_t* __restrict__ send_count_dev) {
+    __shared__ int32_t part_sum[kScanParts][TAMOE_MAX_EXPERTS];
+    __shared__ int32_t kept[TAMOE_MAX_EXPERTS];
+    const int e = threadIdx.x % TAMOE_MAX_EXPERTS;
+    const int part = threadIdx.x / TAMOE_MAX_EXPERTS;
+    const int per_part = (n_entries + kScanParts - 1) / kScanParts;
+    const int q0 = part * per_part;
+    const int q1 = min(n_entries, q0 + per_part);
+    int32_t sum = 0;
+    if (e < N)
+        for (int q = q0; q < q1; ++q) sum += tile_count[(size_t)q * N + e];
+    part_sum[part][e] = sum;
+    __syncthreads();
+    if (e < N) {
+        int32_t run = 0;
+        for (int pp = 0; pp < part; ++pp) run += part_sum[pp][e];
+        for (int q = q0; q < q1; ++q) {
+            const int32_t v = tile_count[(size_t)q * N + e];
+            tile_count[(size_t)q * N + e] = run;
+            run += v;
+        }
+        if (part == 0) {
+            int32_t total = 0;
+            for (int pp = 0; pp < kScanParts; ++pp) total += part_sum[pp][e];
+            const int32_t c = cap[e] < 0 ? 0 : cap[e];
+            kept[e] = total < c ? total : c;
+        }
+    }
+    __syncthreads();
+    if (part == 0 && e < N) {
+        int32_t off = 0;
+        for (int ee = 0; ee < e; ++ee) off += kept[ee];
+        kept_expert[e] = kept[e];
+        expert_offset[e] = off;
+        if (e == N - 1) expert_offset[N] = off + kept[e];
+    }
+    if (part == 1 && e < P) {
+        const int E = N / P;
+        int32_t rows = 0;
+        for (int ee = e * E; ee < (e + 1) * E; ++ee) rows += kept[ee];
+        send_count_dev[e] = rows;
+    }
+}
+
+template <int U>
+__global__ __launch_bounds__(kThreads) void dispatch_scatter_kernel(
+    const vec16* __restrict__ x, const int32_t* __restrict__ idx, const int32_t* __restrict__ cap,
+    const int32_t* __restrict__ tile_base, const int32_t* __restrict__ expert_offset, int64_t S, int N,
+    int k, int n_ct, int row_tile, int cpr, vec16* __restrict__ send, int32_t* __restrict__ slot) {
+    __shared__ int32_t before[TAMOE_MAX_K * TAMOE_MAX_EXPERTS];
+    __shared__ int32_t s_idx[kMaxRowTile * TAMOE_MAX_K];
+    __shared__ int32_t s_slot[kMaxRowTile * TAMOE_MAX_K];
+
+    const int64_t t0 = (int64_t)blockIdx.x * row_tile;
+    const int ct = (int)(t0 / kCountTile);
+    const int64_t tile_begin = (int64_t)ct * kCountTile;
+    const int rows = (int)min((int64_t)row_tile, S - t0);
+    const int pairs = rows * k;
+
+    for (int q = threadIdx.x; q < k * N; q += kThreads) before[q] = 0;
+    for (int p = threadIdx.x; p < pairs; p += kThreads) s_idx[p] = idx[t0 * k + p];
+    __syncthreads();
+    // pairs of this count tile that come before the row tile (same choice j)
+    for (int64_t p = tile_begin * k + threadIdx.x; p < t0 * k; p += kThreads) {
+        const int e = idx[p];
+        const int j = (int)(p % k);
+        if (e >= 0 && e < N) atomicAdd(&before[j * N + e], 1);
+    }
+    __syncthreads();
+    for (int p = threadIdx.x; p < pairs; p += kThreads) {
+        const int e = s_idx[p];
+        const int tl = p / k, j = p - tl * k;
+        int32_t sl = -1;
+        if (e >= 0 && e < N) {
+            int32_t pos = tile_base[((size_t)j * n_ct + ct) * N + e] + before[j * N + e];
+            for (int tt = 0; tt < tl; ++tt) pos += (s_idx[tt * k + j] == e) ? 1 : 0;
+            if (pos < cap[e]) sl = expert_offset[e] + pos;
+        }
+        s_slot[p] = sl;
+        slot[t0 * k + p] = sl;
+    }
+    __syncthreads();
+
+    const int total = rows * cpr;  // 16-byte chunks in this tile (<= 64 rows * 2^16 chunks)
+    const vec16* src = x + (size_t)t0 * cpr;
+    for (int base = 0; base < total; base += kThreads * U) {
+        vec16 v[U];
+        int row[U], col[U];
+        bool live[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int c = base + u * kThreads + threadIdx.x;
+            live[u] = false;
+            row[u] = 0;
+            col[u] = 0;
+            if (c < total) {
+                row[u] = c / cpr;
+                col[u] = c - row[u] * cpr;
+                for (int j = 0; j < k; ++j) live[u] |= s_slot[row[u] * k + j] >= 0;
+            }
+            if (live[u]) v[u] = __builtin_nontemporal_load(src + c);
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            if (!live[u]) continue;
+            for (int j = 0; j < k; ++j) {
+                const int32_t s = s_slot[row[u] * k + j];
+                if (s >= 0) __builtin_nontemporal_store(v[u], send + (size_t)s * cpr + col[u]);
+            }
+        }
+    }
+}
+
+}  // namespace tamoe
+
+using namespace tamoe;
+
+extern "C" int tamoe_dispatch(const void* x, const int32_t* topk_idx, const int32_t* cap, int dtype, int64_t S,
+                              int d, int N, int P, int k, void* send, int32_t* slot, int32_t* kept_expert,
+                              int32_t* expert_offset, int32_t* send_count_dev, void* ws, size_t ws_bytes,
+                              void* stream) {
+    const char* fn = "tamoe_dispatch";
+    clear_error();
+    int rc;
+    if ((rc = check_shape(fn, S, N, P, k)) != TAMOE_OK) return rc;
+    if ((rc = check_rows(fn, dtype, d)) != TAMOE_OK) return rc;
+    if ((rc = check_ptr(fn, "cap", cap, 4)) != TAMOE_OK) return rc;
+    if ((rc = check_ptr(fn, "kept_expert", kept_expert, 4)) != TAMOE_OK) return rc;
+    if ((rc = check_ptr(fn, "expert_offset", expert_offset, 4)) != TAMOE_OK) return rc;
+    if ((rc = check_ptr(fn, "send_count_dev", send_count_dev, 4)) != TAMOE_OK) return rc;
+    if ((rc = check_ptr(fn, "ws", ws, 256)) != TAMOE_OK) return rc;
+    if (S > 0) {
+        if ((rc = check_ptr(fn, "x", x, 16)) != TAMOE_OK) return rc;
+        if ((rc = check_ptr(fn, "topk_idx", topk_idx, 4)) != TAMOE_OK) return rc;
+        if ((rc = check_ptr(fn, "send", send, 16)) != TAMOE_OK) return rc;
+        if ((rc = check_ptr(fn, "slot", slot, 4)) != TAMOE_OK) return rc;
+    }
+    const Workspace lay = workspace_layout(S, N, k);
+    if (ws_bytes < lay.total)
+        return fail(TAMOE_WORKSPACE_TOO_SMALL, "%s: workspace has %zu bytes, %zu needed", fn, ws_bytes, lay.total);
+    const int64_t n_ct = count_tiles(S);
+    if ((int64_t)k * n_ct > (int64_t)1 << 30)
+        return fail(TAMOE_UNSUPPORTED, "%s: too many count tiles (%lld)", fn, (long long)n_ct);
+    const int row_bytes = d * elem_bytes(dtype);
+    const int cpr = row_bytes / 16;
+    if (cpr > 65536) return fail(TAMOE_UNSUPPORTED, "%s: rows longer than 1 MiB are not supported", fn);
+
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    int32_t* tile_count = reinterpret_cast<int32_t*>(static_cast<char*>(ws) + lay.tile_count);
+
+    if (n_ct > 0) {
+        TraceScope tr("dispatch_count_kernel", st);
+        dispatch_count_kernel<<<dim3((unsigned)n_ct), dim3(kThreads), 0, st>>>(topk_idx, S, N, k, (int)n_ct,
+                                                                                tile_count);
+        if ((rc = check_launch(fn, "dispatch_count_kernel")) != TAMOE_OK) return rc;
+    }
+    {
+        TraceScope tr("dispatch_scan_kernel", st);
+        dispatch_scan_kernel<<<dim3(1), dim3(kScanThreads), 0, st>>>(tile_count, cap, N, P, (int)(k * n_ct),
+                                                                      kept_expert, expert_offset, send_count_dev);
+    }
+    if ((rc = check_launch(fn, "dispatch_scan_kernel")) != TAMOE_OK) return rc;
+    if (S > 0) {
+        const int rt = row_tile(S, row_bytes);
+        const int64_t blocks = ceil_div(S, rt);
+        if (blocks > 0x7fffffff) return fail(TAMOE_UNSUPPORTED, "%s: too many row tiles", fn);
+        TraceScope tr("dispatch_scatter_kernel", st);
+        dispatch_scatter_kernel<4><<<dim3((unsigned)blocks), dim3(kThreads), 0, st>>>(
+            static_cast<const vec16*>(x), topk_idx, cap, tile_count, expert_offset, S, N, k, (int)n_ct, rt, cpr,
+            static_cast<vec16*>(send), slot);
+        if ((rc = check_launch(fn, "dispatch_scatter_kernel")) != TAMOE_OK) return rc;
+    }
+    return TAMOE_OK;
+}

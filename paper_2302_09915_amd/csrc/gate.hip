@@ -1,0 +1,503 @@
+// tamoe_gate / tamoe_select: gate scores, softmax, top-k and the load statistics
+// (paper Section 3.1: gate network G with softmax, top-k experts per token, c_ie, m_i;
+// Section 4.1: per-destination-device volume).
+//
+// bf16 path (gate_bf16_kernel): the one dense contraction of the path, on the matrix cores.
+// v_mfma_f32_32x32x16_bf16 with A = a 32-expert block of W (from LDS) and B = 32 tokens of x
+// (straight from global memory, 64 contiguous bytes per lane and 64-element K chunk), so the
+// accumulator tile is [expert][token]: lane l holds, for token (l & 31), the 16 experts
+//     e(v, l) = 8*(v>>2) + 4*(l>>5) + (v&3),   v = 0..15          (+32 per expert block)
+// and the lane pair (l, l^32) holds a token's whole score vector.  Softmax, top-k and the
+// selected weights are therefore computed inside a lane with one cross-lane exchange per step;
+// only the per-expert probability sums need a reduction over the 32 token lanes.
+// The kernel is bound by the HBM read of x (intensity ~N flop/byte), not by the MFMA rate.
+//
+// fp32 path: plain fp32 FMA GEMM into a score buffer, then the same selection code.
+//
+// Determinism: probability sums are reduced in a fixed tree (lanes, wavefronts, workgroups);
+// counts are integers.  A second small kernel folds the per-workgroup partials.
+#include <climits>
+
+#include "internal.h"
+
+namespace tamoe {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+constexpr int kKC = 64;                 // K elements per chunk (128 bytes of a bf16 row)
+constexpr int kLdsRow = kKC * 2 + 16;   // padded LDS row: 16-byte reads of 32 rows stay conflict-free
+
+__device__ __forceinline__ int expert_of(int nb, int v, int half) {
+    return nb * 32 + ((v >> 2) << 3) + (half << 2) + (v & 3);
+}
+
+// Selection on a 32-token tile held in the accumulator layout described above.
+// sc[nb][v]: score of expert_of(nb, v, lane>>5) for token `token` (lane & 31 within the tile).
+// m_wave: LDS, [>= NB*32] floats owned by this wavefront; hist: LDS, [>= NB*32] ints of the block.
+template <int NB>
+__device__ __forceinline__ void select_tile(float (&sc)[NB][16], int lane, int64_t token, bool token_ok, int N,
+                                            int k, float* __restrict__ logits, int32_t* __restrict__ topk_idx,
+                                            float* __restrict__ topk_w, float* m_wave, int32_t* hist) {
+    const int half = lane >> 5;
+    if (logits != nullptr && token_ok) {
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const int e = expert_of(nb, v, half);
+                if (e < N) logits[token * N + e] = sc[nb][v];
+            }
+    }
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v)
+            if (expert_of(nb, v, half) >= N) sc[nb][v] = -INFINITY;
+
+    // top-k: k passes; each pass takes the best score that comes after the previous pick in the
+    // order (score descending, expert index ascending).
+    float sel_v[TAMOE_MAX_K];
+    int sel_i[TAMOE_MAX_K];
+    float last_v = INFINITY;
+    int last_i = -1;
+#pragma unroll
+    for (int j = 0; j < TAMOE_MAX_K; ++j) {
+        sel_v[j] = -INFINITY;
+        sel_i[j] = -1;
+        if (j < k) {
+            float bv = -INFINITY;
+            int bi = INT_MAX;
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) {  // ascending expert index inside a lane
+                    const float a = sc[nb][v];
+                    const int e = expert_of(nb, v, half);
+                    const bool after = (a < last_v) || (a == last_v && e > last_i);
+                    if (after && a > bv) {
+                        bv = a;
+                        bi = e;
+                    }
+                }
+            const float ov = __shfl_xor(bv, 32);
+            const int oi = __shfl_xor(bi, 32);
+            if (ov > bv || (ov == bv && oi < bi)) {
+                bv = ov;
+                bi = oi;
+            }
+            last_v = bv;
+            last_i = bi;
+            sel_v[j] = bv;
+            sel_i[j] = bi == INT_MAX ? -1 : bi;
+        }
+    }
+
+    // softmax: the first pick is the row maximum
+    const float mx = sel_v[0];
+    float part = 0.f;
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            sc[nb][v] = expf(sc[nb][v] - mx);
+            part += sc[nb][v];
+        }
+    const float den = part + __shfl_xor(part, 32);
+    const float inv = 1.0f / den;
+
+    if (half == 0 && token_ok) {
+#pragma unroll
+        for (int j = 0; j < TAMOE_MAX_K; ++j) {
+            if (j < k) {
+                topk_idx[token * k + j] = sel_i[j];
+                topk_w[token * k + j] = expf(sel_v[j] - mx) / den;
+                if (sel_i[j] >= 0 && sel_i[j] < N) atomicAdd(&hist[sel_i[j]], 1);
+            }
+        }
+    }
+
+    // per-expert probability sums over the 32 tokens of the tile
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            float p = token_ok ? sc[nb][v] * inv : 0.f;
+            p += __shfl_xor(p, 1);
+            p += __shfl_xor(p, 2);
+            p += __shfl_xor(p, 4);
+            p += __shfl_xor(p, 8);
+            p += __shfl_xor(p, 16);
+            const int e = expert_of(nb, v, half);
+            if ((lane & 31) == 0 && e < N) m_wave[e] = p;
+        }
+}
+
+// Folds the wavefronts' sums and the block histogram into the per-workgroup partial arrays
+// (expert-major, so that the finalize kernel reads them contiguously).
+template <int NB, int WAVES>
+__device__ __forceinline__ void store_block_partials(const float (*m_w)[NB * 32], const int32_t* hist, int N,
+                                                     int n_blocks, float* __restrict__ m_part,
+                                                     int32_t* __restrict__ c_part) {
+    __syncthreads();
+    for (int e = threadIdx.x; e < N; e += WAVES * 64) {
+        float s = 0.f;
+#pragma unroll
+        for (int w = 0; w < WAVES; ++w) s += m_w[w][e];
+        m_part[(size_t)e * n_blocks + blockIdx.x] = s;
+        c_part[(size_t)e * n_blocks + blockIdx.x] = hist[e];
+    }
+}
+
+template <int NB, int WAVES>
+__global__ __launch_bounds__(WAVES * 64) void gate_bf16_kernel(
+    const uint16_t* __restrict__ x, const uint16_t* __restrict__ w, int64_t S, int d, int N, int k,
+    float* __restrict__ logits, int32_t* __restrict__ topk_idx, float* __restrict__ topk_w,
+    float* __restrict__ m_part, int32_t* __restrict__ c_part, int n_blocks) {
+    constexpr int T = WAVES * 64;
+    constexpr int ROWS = NB * 32;
+    constexpr int UNITS = ROWS * 8 / T;  // 16-byte pieces of the W chunk per thread
+    static_assert(ROWS * 8 % T == 0, "W chunk must split evenly over the threads");
+    __shared__ __attribute__((aligned(16))) unsigned char w_lds[2][ROWS * kLdsRow];
+    __shared__ float m_w[WAVES][ROWS];
+    __shared__ int32_t hist[ROWS];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int r = lane & 31;
+    const int half = lane >> 5;
+    const int64_t token = ((int64_t)blockIdx.x * WAVES + wave) * 32 + r;
+    const bool token_ok = token < S;
+    const uint16_t* xrow = x + (size_t)(token_ok ? token : 0) * d + half * 32;
+
+    for (int e = tid; e < ROWS; e += T) hist[e] = 0;
+    for (int q = tid; q < WAVES * ROWS; q += T) (&m_w[0][0])[q] = 0.f;
+
+    const int n_chunks = (d + kKC - 1) / kKC;
+    const vec16 zero = {0u, 0u, 0u, 0u};
+
+    vec16 wreg[UNITS];
+    vec16 xcur[4], xnext[4];
+
+    auto load_w = [&](int kc) {
+#pragma unroll
+        for (int u = 0; u < UNITS; ++u) {
+            const int unit = tid + u * T;
+            const int row = unit >> 3, piece = unit & 7;
+            const int k0 = kc * kKC + piece * 8;
+            wreg[u] = (row < N && k0 < d) ? *reinterpret_cast<const vec16*>(w + (size_t)row * d + k0) : zero;
+        }
+    };
+    auto store_w = [&](int buf) {
+#pragma unroll
+        for (int u = 0; u < UNITS; ++u) {
+            const int unit = tid + u * T;
+            const int row = unit >> 3, piece = unit & 7;
+            *reinterpret_cast<vec16*>(&w_lds[buf][row * kLdsRow + piece * 16]) = wreg[u];
+        }
+    };
+    auto load_x = [&](int kc, vec16 (&dst)[4]) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int k0 = kc * kKC + half * 32 + i * 8;
+            dst[i] = (token_ok && k0 < d) ? __builtin_nontemporal_load(reinterpret_cast<const vec16*>(xrow + kc * kKC + i * 8))
+                                          : zero;
+        }
+    };
+
+    f32x16 acc[NB];
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[nb][v] = 0.f;
+
+    load_w(0);
+    load_x(0, xcur);
+    store_w(0);
+    __syncthreads();
+
+    int buf = 0;
+    for (int kc = 0; kc < n_chunks; ++kc) {
+        const bool more = kc + 1 < n_chunks;
+        if (more) {
+            load_w(kc + 1);
+            load_x(kc + 1, xnext);
+        }
+        const unsigned char* wl = &w_lds[buf][r * kLdsRow + half * 64];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const bf16x8 b = __builtin_bit_cast(bf16x8, xcur[i]);
+#pragma unroll
+            for (int nb = 0; nb < NB; ++nb) {
+                const bf16x8 a = *reinterpret_cast<const bf16x8*>(wl + nb * 32 * kLdsRow + i * 16);
+                acc[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[nb], 0, 0, 0);
+            }
+        }
+        if (more) store_w(buf ^ 1);
+        __syncthreads();
+#pragma unroll
+        for (int i = 0; i < 4; ++i) xcur[i] = xnext[i];
+        buf ^= 1;
+    }
+
+    float sc[NB][16];
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) sc[nb][v] = acc[nb][v];
+    select_tile<NB>(sc, lane, token, token_ok, N, k, logits, topk_idx, topk_w, m_w[wave], hist);
+    store_block_partials<NB, WAVES>(m_w, hist, N, n_blocks, m_part, c_part);
+}
+
+// fp32 scores: 64 tokens x N experts per workgroup, K in chunks of 32 through LDS, one fp32 FMA
+// per term in ascending K.
+template <int NB>
+__global__ __launch_bounds__(256) void gate_gemm_f32_kernel(const float* __restrict__ x, const float* __restrict__ w,
+                                                            int64_t S, int d, int N, float* __restrict__ logits) {
+    constexpr int ROWS = NB * 32;
+    constexpr int NE = ROWS / 4;
+    __shared__ float xs[64][33];
+    __shared__ float wsm[ROWS][33];
+    const int tid = threadIdx.x;
+    const int tx = tid & 63, ty = tid >> 6;
+    const int64_t t0 = (int64_t)blockIdx.x * 64;
+    float acc[NE];
+#pragma unroll
+    for (int i = 0; i < NE; ++i) acc[i] = 0.f;
+    for (int k0 = 0; k0 < d; k0 += 32) {
+        for (int q = tid; q < 64 * 32; q += 256) {
+            const int row = q >> 5, col = q & 31;
+            const int64_t t = t0 + row;
+            xs[row][col] = (t < S && k0 + col < d) ? x[(size_t)t * d + k0 + col] : 0.f;
+        }
+        for (int q = tid; q < ROWS * 32; q += 256) {
+            const int row = q >> 5, col = q & 31;
+            wsm[row][col] = (row < N && k0 + col < d) ? w[(size_t)row * d + k0 + col] : 0.f;
+        }
+        __syncthreads();
+#pragma unroll 4
+        for (int kk = 0; kk < 32; ++kk) {
+            const float xv = xs[tx][kk];
+#pragma unroll
+            for (int i = 0; i < NE; ++i) acc[i] = __builtin_fmaf(xv, wsm[ty + 4 * i][kk], acc[i]);
+        }
+        __syncthreads();
+    }
+    const int64_t t = t0 + tx;
+    if (t < S) {
+#pragma unroll
+        for (int i = 0; i < NE; ++i) {
+            const int e = ty + 4 * i;
+            if (e < N) logits[(size_t)t * N + e] = acc[i];
+        }
+    }
+}
+
+// Selection stage on a score matrix in memory: 4 wavefronts x 32 tokens per workgroup.
+template <int NB>
+__global__ __launch_bounds__(256) void select_kernel(const float* __restrict__ logits, int64_t S, int N, int k,
+                                                     int32_t* __restrict__ topk_idx, float* __restrict__ topk_w,
+                                                     float* __restrict__ m_part, int32_t* __restrict__ c_part,
+                                                     int n_blocks) {
+    constexpr int ROWS = NB * 32;
+    __shared__ float m_w[4][ROWS];
+    __shared__ int32_t hist[ROWS];
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int half = lane >> 5;
+    const int64_t token = ((int64_t)blockIdx.x * 4 + wave) * 32 + (lane & 31);
+    const bool token_ok = token < S;
+    for (int e = tid; e < ROWS; e += 256) hist[e] = 0;
+    for (int q = tid; q < 4 * ROWS; q += 256) (&m_w[0][0])[q] = 0.f;
+    __syncthreads();
+    float sc[NB][16];
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            const int e = expert_of(nb, v, half);
+            sc[nb][v] = (token_ok && e < N) ? logits[(size_t)token * N + e] : -INFINITY;
+        }
+    select_tile<NB>(sc, lane, token, token_ok, N, k, nullptr, topk_idx, topk_w, m_w[wave], hist);
+    store_block_partials<NB, 4>(m_w, hist, N, n_blocks, m_part, c_part);
+}
+
+// One workgroup per expert: fixed-order sums of the per-workgroup partials.
+__global__ __launch_bounds__(256) void gate_finalize_kernel(const float* __restrict__ m_part,
+                                                            const int32_t* __restrict__ c_part, int n_blocks, int N,
+                                                            int P, int64_t S, float* __restrict__ m,
+                                                            int32_t* __restrict__ c_expert,
+                                                            int32_t* __restrict__ c_device) {
+    __shared__ float fs[256];
+    __shared__ int32_t cs[256];
+    const int e0 = blockIdx.x;
+    const int E = N / P;
+    const int span = (e0 % E == 0) ? E : 1;  // the first expert of a device also sums the device
+    int32_t dev_total = 0;
+    for (int de = 0; de < span; ++de) {
+        const int e = e0 + de;
+        float s = 0.f;
+        int32_t c = 0;
+        for (int i = threadIdx.x; i < n_blocks; i += 256) {
+            s += m_part[(size_t)e * n_blocks + i];
+            c += c_part[(size_t)e * n_blocks + i];
+        }
+        fs[threadIdx.x] = s;
+        cs[threadIdx.x] = c;
+        __syncthreads();
+        for (int stride = 128; stride > 0; stride >>= 1) {
+            if ((int)threadIdx.x < stride) {
+                fs[threadIdx.x] += fs[threadIdx.x + stride];
+                cs[threadIdx.x] += cs[threadIdx.x + stride];
+            }
+            __syncthreads();
+        }
+        if (threadIdx.x == 0) {
+            if (de == 0) {
+                m[e] = S > 0 ? fs[0] / (float)S : 0.f;
+                c_expert[e] = cs[0];
+            }
+            dev_total += cs[0];
+        }
+        __syncthreads();
+    }
+    if (threadIdx.x == 0 && e0 % E == 0) c_device[e0 / E] = dev_total;
+}
+
+// ---- host side ------------------------------------------------------------------------------
+
+template <int NB>
+static void launch_gate_bf16(int waves, int64_t blocks, hipStream_t st, const uint16_t* x, const uint16_t* w,
+                             int64_t S, int d, int N, int k, float* logits, int32_t* topk_idx, float* topk_w,
+                             float* m_part, int32_t* c_part) {
+    const dim3 grid((unsigned)blocks);
+    TraceScope tr("gate_bf16_kernel", st);
+    if (waves == 4)
+        gate_bf16_kernel<NB, 4><<<grid, dim3(256), 0, st>>>(x, w, S, d, N, k, logits, topk_idx, topk_w, m_part, c_part,
+                                                             (int)blocks);
+    else if (waves == 2)
+        gate_bf16_kernel<NB, 2><<<grid, dim3(128), 0, st>>>(x, w, S, d, N, k, logits, topk_idx, topk_w, m_part, c_part,
+                                                             (int)blocks);
+    else
+        gate_bf16_kernel<NB, 1><<<grid, dim3(64), 0, st>>>(x, w, S, d, N, k, logits, topk_idx, topk_w, m_part, c_part,
+                                                            (int)blocks);
+}
+
+static void launch_select(int64_t blocks, hipStream_t st, const float* logits, int64_t S, int N, int k,
+                          int32_t* topk_idx, float* topk_w, float* m_part, int32_t* c_part) {
+    const dim3 grid((unsigned)blocks), block(256);
+    TraceScope tr("select_kernel", st);
+    if (N <= 32)
+        select_kernel<1><<<grid, block, 0, st>>>(logits, S, N, k, topk_idx, topk_w, m_part, c_part, (int)blocks);
+    else if (N <= 64)
+        select_kernel<2><<<grid, block, 0, st>>>(logits, S, N, k, topk_idx, topk_w, m_part, c_part, (int)blocks);
+    else
+        select_kernel<4><<<grid, block, 0, st>>>(logits, S, N, k, topk_idx, topk_w, m_part, c_part, (int)blocks);
+}
+
+static int check_select_outputs(const char* fn, int64_t S, int32_t* topk_idx, float* topk_w, float* m,
+                                int32_t* c_expert, int32_t* c_device, void* ws, size_t ws_bytes,
+                                const Workspace& lay) {
+    int rc;
+    if (S > 0) {
+        if ((rc = check_ptr(fn, "topk_idx", topk_idx, 4)) != TAMOE_OK) return rc;
+        if ((rc = check_ptr(fn, "topk_w", topk_w, 4)) != TAMOE_OK) return rc;
+    }
+    if ((rc = check_ptr(fn, "m", m, 4)) != TAMOE_OK) return rc;
+    if ((rc = check_ptr(fn, "c_expert", c_expert, 4)) != TAMOE_OK) return rc;
+    if ((rc = check_ptr(fn, "c_device", c_device, 4)) != TAMOE_OK) return rc;
+    if ((rc = check_ptr(fn, "ws", ws, 256)) != TAMOE_OK) return rc;
+    if (ws_bytes < lay.total)
+        return fail(TAMOE_WORKSPACE_TOO_SMALL, "%s: workspace has %zu bytes, %zu needed", fn, ws_bytes, lay.total);
+    return TAMOE_OK;
+}
+
+}  // namespace tamoe
+
+using namespace tamoe;
+
+extern "C" int tamoe_select(const float* logits, int64_t S, int N, int P, int k, int32_t* topk_idx, float* topk_w,
+                            float* m, int32_t* c_expert, int32_t* c_device, void* ws, size_t ws_bytes, void* stream) {
+    const char* fn = "tamoe_select";
+    clear_error();
+    int rc;
+    if ((rc = check_shape(fn, S, N, P, k)) != TAMOE_OK) return rc;
+    if (S > 0 && (rc = check_ptr(fn, "logits", logits, 4)) != TAMOE_OK) return rc;
+    const Workspace lay = workspace_layout(S, N, k);
+    if ((rc = check_select_outputs(fn, S, topk_idx, topk_w, m, c_expert, c_device, ws, ws_bytes, lay)) != TAMOE_OK)
+        return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    float* m_part = reinterpret_cast<float*>(static_cast<char*>(ws) + lay.m_part);
+    int32_t* c_part = reinterpret_cast<int32_t*>(static_cast<char*>(ws) + lay.c_part);
+    const int64_t blocks = ceil_div(S, 128);
+    if (blocks > 0) {
+        launch_select(blocks, st, logits, S, N, k, topk_idx, topk_w, m_part, c_part);
+        if ((rc = check_launch(fn, "select_kernel")) != TAMOE_OK) return rc;
+    }
+    {
+        TraceScope tr("gate_finalize_kernel", st);
+        gate_finalize_kernel<<<dim3(N), dim3(256), 0, st>>>(m_part, c_part, (int)blocks, N, P, S, m, c_expert,
+                                                            c_device);
+    }
+    return check_launch(fn, "gate_finalize_kernel");
+}
+
+extern "C" int tamoe_gate(const void* x, const void* w, int dtype, int64_t S, int d, int N, int P, int k,
+                          float* logits, int32_t* topk_idx, float* topk_w, float* m, int32_t* c_expert,
+                          int32_t* c_device, void* ws, size_t ws_bytes, void* stream) {
+    const char* fn = "tamoe_gate";
+    clear_error();
+    int rc;
+    if ((rc = check_shape(fn, S, N, P, k)) != TAMOE_OK) return rc;
+    if ((rc = check_rows(fn, dtype, d)) != TAMOE_OK) return rc;
+    if (S > 0) {
+        if ((rc = check_ptr(fn, "x", x, 16)) != TAMOE_OK) return rc;
+        if ((rc = check_ptr(fn, "w", w, 16)) != TAMOE_OK) return rc;
+    }
+    const Workspace lay = workspace_layout(S, N, k);
+    if ((rc = check_select_outputs(fn, S, topk_idx, topk_w, m, c_expert, c_device, ws, ws_bytes, lay)) != TAMOE_OK)
+        return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    float* m_part = reinterpret_cast<float*>(static_cast<char*>(ws) + lay.m_part);
+    int32_t* c_part = reinterpret_cast<int32_t*>(static_cast<char*>(ws) + lay.c_part);
+    int64_t blocks = 0;
+    if (S > 0 && dtype == TAMOE_BF16) {
+        const int waves = gate_waves(S);
+        blocks = gate_blocks(S);
+        if (blocks > 0x7fffffff) return fail(TAMOE_UNSUPPORTED, "%s: too many token tiles", fn);
+        const uint16_t* xb = static_cast<const uint16_t*>(x);
+        const uint16_t* wb = static_cast<const uint16_t*>(w);
+        if (N <= 32)
+            launch_gate_bf16<1>(waves, blocks, st, xb, wb, S, d, N, k, logits, topk_idx, topk_w, m_part, c_part);
+        else if (N <= 64)
+            launch_gate_bf16<2>(waves, blocks, st, xb, wb, S, d, N, k, logits, topk_idx, topk_w, m_part, c_part);
+        else
+            launch_gate_bf16<4>(waves, blocks, st, xb, wb, S, d, N, k, logits, topk_idx, topk_w, m_part, c_part);
+        if ((rc = check_launch(fn, "gate_bf16_kernel")) != TAMOE_OK) return rc;
+    } else if (S > 0) {
+        float* lg = logits != nullptr ? logits : reinterpret_cast<float*>(static_cast<char*>(ws) + lay.logits);
+        const dim3 grid((unsigned)ceil_div(S, 64)), block(256);
+        const float* xf = static_cast<const float*>(x);
+        const float* wf = static_cast<const float*>(w);
+        {
+            TraceScope tr("gate_gemm_f32_kernel", st);
+            if (N <= 32)
+                gate_gemm_f32_kernel<1><<<grid, block, 0, st>>>(xf, wf, S, d, N, lg);
+            else if (N <= 64)
+                gate_gemm_f32_kernel<2><<<grid, block, 0, st>>>(xf, wf, S, d, N, lg);
+            else
+                gate_gemm_f32_kernel<4><<<grid, block, 0, st>>>(xf, wf, S, d, N, lg);
+        }
+        if ((rc = check_launch(fn, "gate_gemm_f32_kernel")) != TAMOE_OK) return rc;
+        blocks = ceil_div(S, 128);
+        launch_select(blocks, st, lg, S, N, k, topk_idx, topk_w, m_part, c_part);
+        if ((rc = check_launch(fn, "select_kernel")) != TAMOE_OK) return rc;
+    }
+    {
+        TraceScope tr("gate_finalize_kernel", st);
+        gate_finalize_kernel<<<dim3(N), dim3(256), 0, st>>>(m_part, c_part, (int)blocks, N, P, S, m, c_expert,
+                                                            c_device);
+    }
+    return check_launch(fn, "gate_finalize_kernel");
+}

@@ -1,0 +1,254 @@
+// Host side of libtamoe: error reporting, argument checks, workspace layout and the setup-time
+// derivation of the target dispatch pattern.
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <vector>
+
+#include "internal.h"
+
+namespace tamoe {
+
+static thread_local char g_err[512] = "";
+
+int fail(int code, const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+void clear_error() { g_err[0] = '\0'; }
+
+int gate_waves(int64_t S) {
+    // aim for at least two workgroups per compute unit (256 CUs)
+    if (ceil_div(S, 128) >= 512) return 4;
+    if (ceil_div(S, 64) >= 512) return 2;
+    return 1;
+}
+
+int row_tile(int64_t S, int row_bytes) {
+    // Rows per scatter/combine workgroup: small enough for >= ~4 workgroups per compute unit,
+    // large enough that a workgroup moves at least 16 KiB.
+    int tile = 64;
+    while (tile > 4 && ceil_div(S, tile) < 1024) tile >>= 1;
+    while (tile < 64 && (int64_t)tile * row_bytes < 16384) tile <<= 1;
+    return tile;
+}
+
+Workspace workspace_layout(int64_t S, int N, int k) {
+    Workspace w{};
+    size_t off = 0;
+    const size_t gb = (size_t)gate_blocks_max(S);
+    w.m_part = off;
+    off = align_up(off + gb * N * sizeof(float), 256);
+    w.c_part = off;
+    off = align_up(off + gb * N * sizeof(int32_t), 256);
+    w.logits = off;
+    off = align_up(off + (size_t)S * N * sizeof(float), 256);
+    w.tile_count = off;
+    off = align_up(off + (size_t)k * count_tiles(S) * N * sizeof(int32_t), 256);
+    w.total = off < 256 ? 256 : off;
+    return w;
+}
+
+int check_shape(const char* fn, int64_t S, int N, int P, int k) {
+    if (S < 0) return fail(TAMOE_INVALID_ARG, "%s: S = %lld is negative", fn, (long long)S);
+    if (N <= 0 || P <= 0 || k <= 0)
+        return fail(TAMOE_INVALID_ARG, "%s: N = %d, P = %d, k = %d must all be positive", fn, N, P, k);
+    if (k > N) return fail(TAMOE_INVALID_ARG, "%s: k = %d exceeds N = %d", fn, k, N);
+    if (N % P != 0) return fail(TAMOE_INVALID_ARG, "%s: N = %d is not a multiple of P = %d", fn, N, P);
+    if (N > TAMOE_MAX_EXPERTS)
+        return fail(TAMOE_UNSUPPORTED, "%s: N = %d exceeds the limit of %d experts", fn, N, TAMOE_MAX_EXPERTS);
+    if (k > TAMOE_MAX_K) return fail(TAMOE_UNSUPPORTED, "%s: k = %d exceeds the limit of %d", fn, k, TAMOE_MAX_K);
+    if (S * (int64_t)k >= (int64_t)1 << 31)
+        return fail(TAMOE_UNSUPPORTED, "%s: S*k = %lld does not fit int32 slots", fn, (long long)(S * k));
+    return TAMOE_OK;
+}
+
+int check_rows(const char* fn, int dtype, int d) {
+    if (dtype != TAMOE_F32 && dtype != TAMOE_BF16)
+        return fail(TAMOE_UNSUPPORTED, "%s: dtype %d is neither TAMOE_F32 nor TAMOE_BF16", fn, dtype);
+    if (d <= 0) return fail(TAMOE_INVALID_ARG, "%s: d = %d must be positive", fn, d);
+    if (((int64_t)d * elem_bytes(dtype)) % 16 != 0)
+        return fail(TAMOE_UNSUPPORTED, "%s: a row of d = %d elements is not a multiple of 16 bytes", fn, d);
+    return TAMOE_OK;
+}
+
+int check_ptr(const char* fn, const char* name, const void* p, size_t align) {
+    if (p == nullptr) return fail(TAMOE_INVALID_ARG, "%s: %s is NULL", fn, name);
+    if (align > 1 && (reinterpret_cast<uintptr_t>(p) % align) != 0)
+        return fail(TAMOE_INVALID_ARG, "%s: %s is not %zu-byte aligned", fn, name, align);
+    return TAMOE_OK;
+}
+
+int check_launch(const char* fn, const char* kernel) {
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess)
+        return fail(TAMOE_HIP_ERROR, "%s: launch of %s failed: %s", fn, kernel, hipGetErrorString(e));
+    return TAMOE_OK;
+}
+
+// ---- kernel timing aid --------------------------------------------------------------------
+bool g_trace_on = false;
+namespace {
+struct TraceRecord {
+    const char* kernel;
+    hipEvent_t begin, end;
+};
+std::vector<TraceRecord> g_records;   // capacity fixed by tamoe_trace_start
+size_t g_used = 0;
+bool g_open = false;                  // a begin without its end
+}  // namespace
+
+void trace_begin(const char* kernel, hipStream_t st) {
+    if (g_used >= g_records.size()) {
+        g_trace_on = false;
+        return;
+    }
+    g_records[g_used].kernel = kernel;
+    g_open = hipEventRecord(g_records[g_used].begin, st) == hipSuccess;
+}
+
+void trace_end(hipStream_t st) {
+    if (!g_open) return;
+    g_open = false;
+    if (hipEventRecord(g_records[g_used].end, st) == hipSuccess) ++g_used;
+    if (g_used >= g_records.size()) g_trace_on = false;
+}
+
+}  // namespace tamoe
+
+using namespace tamoe;
+
+extern "C" int tamoe_trace_clear(void) {
+    g_trace_on = false;
+    for (auto& r : g_records) {
+        (void)hipEventDestroy(r.begin);
+        (void)hipEventDestroy(r.end);
+    }
+    g_records.clear();
+    g_used = 0;
+    g_open = false;
+    return TAMOE_OK;
+}
+
+extern "C" int tamoe_trace_start(int max_launches) {
+    clear_error();
+    if (max_launches <= 0 || max_launches > (1 << 20))
+        return fail(TAMOE_INVALID_ARG, "tamoe_trace_start: max_launches = %d outside (0, 2^20]", max_launches);
+    tamoe_trace_clear();
+    g_records.reserve((size_t)max_launches);
+    for (int i = 0; i < max_launches; ++i) {
+        TraceRecord r{nullptr, nullptr, nullptr};
+        if (hipEventCreate(&r.begin) != hipSuccess || hipEventCreate(&r.end) != hipSuccess) {
+            tamoe_trace_clear();
+            return fail(TAMOE_HIP_ERROR, "tamoe_trace_start: hipEventCreate failed");
+        }
+        g_records.push_back(r);
+    }
+    g_trace_on = true;
+    return TAMOE_OK;
+}
+
+extern "C" int tamoe_trace_stop(void) {
+    clear_error();
+    g_trace_on = false;
+    if (g_used > 0 && hipEventSynchronize(g_records[g_used - 1].end) != hipSuccess)
+        return -fail(TAMOE_HIP_ERROR, "tamoe_trace_stop: hipEventSynchronize failed");
+    return (int)g_used;
+}
+
+extern "C" int tamoe_trace_get(int i, char* name, size_t name_len, float* ms) {
+    clear_error();
+    if (i < 0 || (size_t)i >= g_used) return fail(TAMOE_INVALID_ARG, "tamoe_trace_get: record %d does not exist", i);
+    if (name != nullptr && name_len > 0) {
+        std::snprintf(name, name_len, "%s", g_records[i].kernel);
+    }
+    if (ms != nullptr && hipEventElapsedTime(ms, g_records[i].begin, g_records[i].end) != hipSuccess)
+        return fail(TAMOE_HIP_ERROR, "tamoe_trace_get: hipEventElapsedTime failed");
+    return TAMOE_OK;
+}
+
+extern "C" int tamoe_version(void) { return TAMOE_VERSION; }
+
+extern "C" const char* tamoe_last_error(void) { return g_err; }
+
+extern "C" size_t tamoe_workspace_bytes(int64_t S, int d, int N, int P, int k, int dtype) {
+    (void)d; (void)P; (void)dtype;
+    if (S < 0 || N <= 0 || k <= 0) return 0;
+    return workspace_layout(S, N, k).total;
+}
+
+// Setup stage.  Per-level means of the profiled inverse bandwidths, then the closed-form target
+// pattern of Section 4.2 (volume sent over a link inversely proportional to its inverse
+// bandwidth, scaled so that the row sums to k*S), the L1-normalised reciprocal as penalty
+// (Section 4.3) and the local capacities.
+extern "C" int tamoe_topo_pattern(const double* beta, const int32_t* level, int P, int N, int rank,
+                                  int k, int64_t S, double capacity_factor, int cap_mode,
+                                  double* c_hat, float* penalty, int32_t* cap) {
+    const char* fn = "tamoe_topo_pattern";
+    clear_error();
+    if (beta == nullptr) return fail(TAMOE_INVALID_ARG, "%s: beta is NULL", fn);
+    if (N <= 0 || P <= 0 || k <= 0 || S <= 0)
+        return fail(TAMOE_INVALID_ARG, "%s: N = %d, P = %d, k = %d, S = %lld must all be positive", fn, N, P, k,
+                    (long long)S);
+    if (N % P != 0) return fail(TAMOE_INVALID_ARG, "%s: N = %d is not a multiple of P = %d", fn, N, P);
+    if (k > N) return fail(TAMOE_INVALID_ARG, "%s: k = %d exceeds N = %d", fn, k, N);
+    if (rank < 0 || rank >= P) return fail(TAMOE_INVALID_ARG, "%s: rank = %d outside [0, %d)", fn, rank, P);
+    if (cap_mode != TAMOE_CAP_UNIFORM && cap_mode != TAMOE_CAP_PROPORTIONAL)
+        return fail(TAMOE_INVALID_ARG, "%s: unknown cap_mode %d", fn, cap_mode);
+    if (!(capacity_factor > 0.0) || !std::isfinite(capacity_factor))
+        return fail(TAMOE_INVALID_ARG, "%s: capacity_factor must be positive and finite", fn);
+    for (int q = 0; q < P * P; ++q) {
+        if (!(beta[q] > 0.0) || !std::isfinite(beta[q]))
+            return fail(TAMOE_INVALID_ARG, "%s: beta[%d][%d] = %g is not a positive finite number", fn, q / P, q % P,
+                        beta[q]);
+        if (level != nullptr && level[q] < 0)
+            return fail(TAMOE_INVALID_ARG, "%s: level[%d][%d] = %d is negative", fn, q / P, q % P, level[q]);
+    }
+
+    // Row `rank` of the hierarchical matrix.
+    std::vector<double> row(beta + (size_t)rank * P, beta + (size_t)(rank + 1) * P);
+    if (level != nullptr) {
+        int n_levels = 0;
+        for (int q = 0; q < P * P; ++q) n_levels = level[q] + 1 > n_levels ? level[q] + 1 : n_levels;
+        std::vector<double> pair_sum(n_levels, 0.0), self_sum(n_levels, 0.0);
+        std::vector<int64_t> pair_cnt(n_levels, 0), self_cnt(n_levels, 0);
+        for (int a = 0; a < P; ++a) {
+            for (int b = a; b < P; ++b) {
+                const int l = level[a * P + b];
+                if (a == b) { self_sum[l] += beta[a * P + b]; self_cnt[l] += 1; }
+                else        { pair_sum[l] += beta[a * P + b]; pair_cnt[l] += 1; }
+            }
+        }
+        for (int j = 0; j < P; ++j) {
+            const int l = level[rank * P + j];
+            row[j] = pair_cnt[l] > 0 ? pair_sum[l] / (double)pair_cnt[l] : self_sum[l] / (double)self_cnt[l];
+        }
+    }
+
+    const int E = N / P;
+    double inv_sum = 0.0;
+    for (int j = 0; j < P; ++j) inv_sum += 1.0 / row[j];
+    const double share_unit = (double)k * (double)S / ((double)E * inv_sum);  // rows * beta per expert
+    std::vector<double> target(N);
+    double recip_sum = 0.0;
+    for (int e = 0; e < N; ++e) {
+        target[e] = share_unit / row[e / E];
+        recip_sum += 1.0 / target[e];
+    }
+    for (int e = 0; e < N; ++e) {
+        if (c_hat) c_hat[e] = target[e];
+        if (penalty) penalty[e] = (float)((1.0 / target[e]) / recip_sum);
+        if (cap) {
+            const double v = cap_mode == TAMOE_CAP_UNIFORM ? capacity_factor * (double)k * (double)S / (double)N
+                                                           : capacity_factor * target[e];
+            const double c = std::ceil(v - 1e-9);
+            if (c > 2147483647.0) return fail(TAMOE_UNSUPPORTED, "%s: capacity %g does not fit int32", fn, c);
+            cap[e] = (int32_t)c;
+        }
+    }
+    return TAMOE_OK;
+}

@@ -1,0 +1,74 @@
+// Internal declarations shared by the translation units of libtamoe (not part of the ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cstdarg>
+#include <cstddef>
+#include <cstdint>
+
+#include "tamoe.h"
+
+namespace tamoe {
+
+// 16 bytes as a native vector, the unit of every row copy (global_load/store_dwordx4).
+typedef uint32_t vec16 __attribute__((ext_vector_type(4)));
+
+// Records the message returned by tamoe_last_error() and passes `code` through.
+int fail(int code, const char* fmt, ...) __attribute__((format(printf, 2, 3)));
+void clear_error();
+
+inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+inline int elem_bytes(int dtype) { return dtype == TAMOE_F32 ? 4 : 2; }
+
+// ---- launch geometry (host side; the kernels receive what they need as arguments) ----------
+
+// Gate: a workgroup of 64*waves threads scores 32*waves tokens (one 32-token MFMA column block
+// per wavefront).  More wavefronts per workgroup share one LDS copy of the W tile; fewer give
+// more workgroups when S is small.
+int gate_waves(int64_t S);
+inline int64_t gate_blocks(int64_t S) { return S == 0 ? 0 : ceil_div(S, 32 * (int64_t)gate_waves(S)); }
+// Upper bound of gate_blocks over every choice of waves.
+inline int64_t gate_blocks_max(int64_t S) { return ceil_div(S, 32); }
+
+// Dispatch: pairs are counted per "count tile" of kCountTile tokens; a scatter workgroup moves
+// the rows of a "row tile" of row_tile(S) tokens (a divisor of kCountTile).
+constexpr int kCountTile = 1024;
+int row_tile(int64_t S, int row_bytes);
+inline int64_t count_tiles(int64_t S) { return ceil_div(S, kCountTile); }
+
+// ---- workspace layout -----------------------------------------------------------------------
+struct Workspace {
+    size_t m_part;      // float  [N][gate_blocks_max]   per-workgroup sums of gate probabilities
+    size_t c_part;      // int32  [N][gate_blocks_max]   per-workgroup selection counts
+    size_t logits;      // float  [S][N]                 fp32-path scores when the caller wants none
+    size_t tile_count;  // int32  [k][count_tiles][N]    pair counts, then their exclusive prefix
+    size_t total;
+};
+Workspace workspace_layout(int64_t S, int N, int k);
+
+// Common argument checks.  Return TAMOE_OK or a failure already recorded with fail().
+int check_shape(const char* fn, int64_t S, int N, int P, int k);
+int check_rows(const char* fn, int dtype, int d);
+int check_ptr(const char* fn, const char* name, const void* p, size_t align);
+int check_launch(const char* fn, const char* kernel);
+
+// Brackets one kernel launch with a pair of events while a trace is running (tamoe_trace_start);
+// a single branch otherwise.
+extern bool g_trace_on;
+void trace_begin(const char* kernel, hipStream_t st);
+void trace_end(hipStream_t st);
+struct TraceScope {
+    hipStream_t st;
+    bool on;
+    TraceScope(const char* kernel, hipStream_t s) : st(s), on(g_trace_on) {
+        if (on) trace_begin(kernel, st);
+    }
+    ~TraceScope() {
+        if (on) trace_end(st);
+    }
+};
+
+}  // namespace tamoe

@@ -1,0 +1,175 @@
+"""CPU-side checks of the C-ABI library: it loads, exports every declared symbol, rejects bad
+arguments with the documented status codes before touching a GPU, and its host-side setup
+function agrees with the oracle."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import tamoe_workloads as W
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def T():
+    import paper_2302_09915_amd as T
+
+    if not os.path.exists(T.LIB_PATH):
+        from paper_2302_09915_amd import build
+
+        build.build()
+    T.lib()
+    return T
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "tamoe.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(tamoe_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(T):
+    names = _declared_symbols()
+    assert set(names) == set(T.EXPORTS), names
+    L = ctypes.CDLL(T.LIB_PATH)
+    for n in names:
+        assert getattr(L, n) is not None
+    assert T.tamoe_version() == 1
+
+
+def test_limits_match_header(T):
+    text = open(os.path.join(ROOT, "include", "tamoe.h")).read()
+    assert int(re.search(r"#define TAMOE_MAX_EXPERTS (\d+)", text).group(1)) == T.MAX_EXPERTS
+    assert int(re.search(r"#define TAMOE_MAX_K (\d+)", text).group(1)) == T.MAX_K
+
+
+# ---- host setup function against the oracle -------------------------------------------------
+@pytest.mark.parametrize("name", list(W.WORKLOADS))
+@pytest.mark.parametrize("cap_mode", [0, 1])
+def test_topo_pattern_matches_oracle(T, oracle, name, cap_mode):
+    wl = W.WORKLOADS[name]
+    beta, level = W.topology(wl)
+    for rank in (0, wl.P // 2 + 1, wl.P - 1):
+        c_hat, pen, cap = T.tamoe_topo_pattern(beta, level, wl.P, wl.N, rank, wl.k, wl.S, wl.capacity_factor, cap_mode)
+        oc, op, ocap = oracle.setup(beta, level, wl.N, rank, wl.k, wl.S, wl.capacity_factor, cap_mode)
+        np.testing.assert_allclose(c_hat, oc, rtol=1e-13)
+        np.testing.assert_allclose(pen, op, rtol=1e-6)           # float output
+        np.testing.assert_array_equal(cap, ocap)
+
+
+def test_topo_pattern_smooths_noisy_tables_like_the_oracle(T, oracle):
+    noisy, level = W.noisy_topology(4, 4, 8.0, seed=21)
+    level = level.copy()
+    np.fill_diagonal(level, 2)                      # self transfers on a level of their own
+    noisy[np.diag_indices(16)] *= 0.1
+    for rank in (0, 9):
+        c_hat, pen, cap = T.tamoe_topo_pattern(noisy, level, 16, 32, rank, 2, 4096, 1.25, 1)
+        oc, op, ocap = oracle.setup(noisy, level, 32, rank, 2, 4096, 1.25, 1)
+        np.testing.assert_allclose(c_hat, oc, rtol=1e-12)
+        np.testing.assert_allclose(pen, op, rtol=1e-6)
+        np.testing.assert_array_equal(cap, ocap)
+    # without a level table the raw row is used
+    c_hat, _, _ = T.tamoe_topo_pattern(noisy, None, 16, 16, 3, 1, 1000, 1.0, 0)
+    np.testing.assert_allclose(c_hat, oracle.target_pattern(noisy, 16, 3, 1, 1000), rtol=1e-13)
+
+
+def test_topo_pattern_rejects_bad_arguments(T):
+    beta, level = W.two_tier_topology(2, 2, 4.0)
+    ok = dict(beta=beta, level=level, P=4, N=8, rank=0, k=2, S=100, capacity_factor=1.0, cap_mode=0)
+
+    def call(**kw):
+        a = dict(ok, **kw)
+        return T.tamoe_topo_pattern(a["beta"], a["level"], a["P"], a["N"], a["rank"], a["k"], a["S"],
+                                    a["capacity_factor"], a["cap_mode"])
+
+    call()
+    for bad in (dict(rank=4), dict(rank=-1), dict(N=6), dict(k=9), dict(S=0), dict(cap_mode=5),
+                dict(capacity_factor=0.0), dict(capacity_factor=float("nan"))):
+        with pytest.raises(T.TamoeError) as ei:
+            call(**bad)
+        assert ei.value.status == T.INVALID_ARG, bad
+        assert "tamoe_topo_pattern" in ei.value.message
+    b2 = beta.copy(); b2[1, 2] = 0.0
+    with pytest.raises(T.TamoeError):
+        call(beta=b2)
+    b3 = beta.copy(); b3[0, 0] = float("inf")
+    with pytest.raises(T.TamoeError):
+        call(beta=b3)
+    l2 = level.copy(); l2[0, 1] = -1
+    with pytest.raises(T.TamoeError):
+        call(level=l2)
+
+
+# ---- argument checks of the device entry points (they fail before any HIP call) -------------
+def test_device_entry_points_reject_bad_shapes_without_a_gpu(T):
+    L = T.lib()
+    one = ctypes.c_void_p(256)      # a non-null, aligned, never dereferenced address
+    odd = ctypes.c_void_p(260)
+    big = 1 << 30
+
+    def status(rc, code, needle):
+        assert rc == code, (rc, T.tamoe_last_error())
+        assert needle in T.tamoe_last_error()
+
+    # gate
+    status(L.tamoe_gate(one, one, 1, 64, 64, 8, 4, 9, None, one, one, one, one, one, one, big, None),
+           T.INVALID_ARG, "k = 9 exceeds N")
+    status(L.tamoe_gate(one, one, 1, 64, 64, 6, 4, 1, None, one, one, one, one, one, one, big, None),
+           T.INVALID_ARG, "not a multiple of P")
+    status(L.tamoe_gate(one, one, 1, 64, 64, 256, 4, 1, None, one, one, one, one, one, one, big, None),
+           T.UNSUPPORTED, "limit of 128 experts")
+    status(L.tamoe_gate(one, one, 1, 64, 64, 16, 4, 12, None, one, one, one, one, one, one, big, None),
+           T.UNSUPPORTED, "k = 12 exceeds the limit")
+    status(L.tamoe_gate(one, one, 7, 64, 64, 8, 4, 1, None, one, one, one, one, one, one, big, None),
+           T.UNSUPPORTED, "dtype 7")
+    status(L.tamoe_gate(one, one, 1, 64, 60, 8, 4, 1, None, one, one, one, one, one, one, big, None),
+           T.UNSUPPORTED, "multiple of 16 bytes")
+    status(L.tamoe_gate(None, one, 1, 64, 64, 8, 4, 1, None, one, one, one, one, one, one, big, None),
+           T.INVALID_ARG, "x is NULL")
+    status(L.tamoe_gate(odd, one, 1, 64, 64, 8, 4, 1, None, one, one, one, one, one, one, big, None),
+           T.INVALID_ARG, "x is not 16-byte aligned")
+    status(L.tamoe_gate(one, one, 1, 64, 64, 8, 4, 1, None, one, one, one, one, one, one, 16, None),
+           T.WORKSPACE_TOO_SMALL, "workspace has 16 bytes")
+    status(L.tamoe_gate(one, one, 1, -1, 64, 8, 4, 1, None, one, one, one, one, one, one, big, None),
+           T.INVALID_ARG, "negative")
+    # select
+    status(L.tamoe_select(None, 64, 8, 4, 1, one, one, one, one, one, one, big, None), T.INVALID_ARG, "logits is NULL")
+    # aux loss
+    status(L.tamoe_aux_loss(one, one, None, 8, 4, 0, one, None), T.INVALID_ARG, "S = 0")
+    status(L.tamoe_aux_loss(one, one, None, 8, 4, 10, None, None), T.INVALID_ARG, "loss is NULL")
+    # dispatch
+    status(L.tamoe_dispatch(one, one, None, 1, 64, 64, 8, 4, 2, one, one, one, one, one, one, big, None),
+           T.INVALID_ARG, "cap is NULL")
+    status(L.tamoe_dispatch(one, one, one, 1, 64, 64, 8, 4, 2, one, one, one, one, one, one, 0, None),
+           T.WORKSPACE_TOO_SMALL, "needed")
+    status(L.tamoe_dispatch(one, one, one, 1, 1 << 30, 64, 8, 4, 2, one, one, one, one, one, one, big, None),
+           T.UNSUPPORTED, "int32")
+    # combine
+    status(L.tamoe_combine(one, 10, one, one, 1, 64, 64, 0, one, None), T.INVALID_ARG, "k = 0")
+    status(L.tamoe_combine(one, 10, one, one, 1, 64, 64, 2, None, None), T.INVALID_ARG, "y is NULL")
+    status(L.tamoe_combine(one, 10, one, one, 0, 64, 6, 2, one, None), T.UNSUPPORTED, "16 bytes")
+
+
+def test_workspace_size_is_monotone_and_covers_the_configs(T):
+    prev = 0
+    for S in (0, 1, 100, 4096, 65536):
+        b = T.tamoe_workspace_bytes(S, 1024, 64, 64, 2, T.BF16)
+        assert b >= prev and b % 256 == 0 and b > 0
+        prev = b
+    wl = W.WORKLOADS["large"]
+    assert T.tamoe_workspace_bytes(wl.S, wl.d, wl.N, wl.P, wl.k, wl.dtype) < 64 << 20
+
+
+def test_binding_has_no_cpu_fallback(T, monkeypatch):
+    """A missing library must raise, never route anywhere else."""
+    import paper_2302_09915_amd as pkg
+
+    monkeypatch.setattr(pkg, "_lib", None)
+    monkeypatch.setattr(pkg, "LIB_PATH", os.path.join(ROOT, "no_such_dir", "libtamoe.so"))
+    with pytest.raises(ImportError):
+        pkg.lib()
+    src = open(os.path.join(ROOT, "paper_2302_09915_amd", "__init__.py")).read()
+    assert "import oracle" not in src and "from oracle" not in src

@@ -1,0 +1,375 @@
+"""Parity of the HIP path (through the C ABI) against the CPU oracle on a real MI355X.
+
+Staging (same seeded inputs on both sides):
+  A  scores: GPU fp32 logits vs oracle fp64 logits, normwise and elementwise, tol 1e-3 (bf16
+     inputs) / 1e-5 (fp32 inputs);
+  B  everything decided from the scores is compared with the oracle re-run on the GPU's own fp32
+     scores: indices, counts, slots, kept, offsets, per-device rows bit-exact; weights, mean
+     probabilities and the losses within 1e-5 relative;
+  C  the send buffer is a bit copy;
+  D  combine: against the oracle's fp64 sum of the same rows with the GPU's fp32 weights: within
+     half an ulp of the storage type plus the fp32 accumulation error, and equal to the oracle's
+     once-rounded output in all but a tiny fraction of elements (1-ulp flips at rounding ties);
+  E  end to end: the loss from the oracle's own scores vs the GPU's, 1e-3 (bf16) / 1e-5 (fp32).
+"""
+import math
+
+import numpy as np
+import pytest
+
+import tamoe_workloads as W
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+@pytest.fixture(scope="module")
+def T():
+    if not torch.cuda.is_available():
+        pytest.fail("these tests need a GPU (run with -m 'not gpu' elsewhere)")
+    import paper_2302_09915_amd as T
+
+    T.lib()          # raises if the HIP library is missing: there is no fallback
+    return T
+
+
+# ---------------------------------------------------------------------------
+# helpers
+# ---------------------------------------------------------------------------
+def to_dev(a: np.ndarray, dtype: int):
+    t = torch.from_numpy(a)
+    if dtype == W.BF16:
+        t = t.view(torch.int16).view(torch.bfloat16)
+    return t.cuda()
+
+
+def to_host(t, dtype: int) -> np.ndarray:
+    if dtype == W.BF16:
+        return t.view(torch.int16).cpu().numpy().view(np.uint16)
+    return t.cpu().numpy()
+
+
+def ulp_of(v: np.ndarray, dtype: int) -> np.ndarray:
+    """Spacing of the storage type at |v| (float64 in, float64 out)."""
+    mant = 7 if dtype == W.BF16 else 23
+    a = np.abs(v)
+    e = np.floor(np.log2(np.maximum(a, 2.0 ** -126)))
+    return 2.0 ** (e - mant)
+
+
+def check_logits(gpu: np.ndarray, ref: np.ndarray, dtype: int):
+    tol = 1e-3 if dtype == W.BF16 else 1e-5
+    diff = np.abs(gpu.astype(np.float64) - ref)
+    assert diff.max() <= tol * np.abs(ref).max()
+    rms = math.sqrt(float((ref ** 2).mean()))
+    assert (diff <= tol * (np.abs(ref) + rms)).all()
+
+
+def check_routing(T, oracle, g, ref, N, k):
+    """g: GPU outputs (numpy), ref: oracle.route_from_logits on the GPU's scores."""
+    np.testing.assert_array_equal(g["topk_idx"], ref["topk_idx"])
+    np.testing.assert_array_equal(g["c_expert"], ref["c_expert"])
+    np.testing.assert_array_equal(g["c_device"], ref["c_device"])
+    np.testing.assert_allclose(g["topk_w"], ref["topk_w"], rtol=1e-5, atol=1e-30)
+    np.testing.assert_allclose(g["m"], ref["m"], rtol=1e-5, atol=1e-12)
+    np.testing.assert_array_equal(g["slot"], ref["slot"])
+    np.testing.assert_array_equal(g["kept_expert"], ref["kept"])
+    np.testing.assert_array_equal(g["expert_offset"], ref["off"])
+    np.testing.assert_array_equal(g["send_count_dev"], ref["send_count_dev"])
+    assert g["l_topo"] == pytest.approx(ref["l_topo"], rel=1e-5)
+    assert g["l_aux"] == pytest.approx(ref["l_aux"], rel=1e-5)
+    assert g["c_expert"].sum() == g["topk_idx"].size
+
+
+def check_combine(y_gpu: np.ndarray, y_exact: np.ndarray, y_ref: np.ndarray, mag: np.ndarray, dtype: int, k: int):
+    """mag = sum_j |w_j * recv_j| elementwise (bounds the fp32 accumulation error)."""
+    yv = W.storage_to_f64(y_gpu, dtype)
+    arith = 4.0 * k * 2.0 ** -24 * mag
+    bound = 0.5 * ulp_of(y_exact, dtype) + arith + 2.0 ** -149
+    assert (np.abs(yv - y_exact) <= bound).all()
+    flips = (y_gpu != y_ref)
+    # +0 / -0 are the same value
+    flips &= ~((W.storage_to_f64(y_ref, dtype) == 0) & (yv == 0))
+    assert flips.mean() <= 1e-3
+
+
+def gpu_path(T, wl_like, x_np, w_np, penalty, cap, want_logits=True):
+    """Runs gate -> losses -> dispatch -> combine (identity expert) through the C ABI."""
+    dt = wl_like["dtype"]
+    N, P, k = wl_like["N"], wl_like["P"], wl_like["k"]
+    x = to_dev(x_np, dt)
+    w = to_dev(w_np, dt)
+    S, d = x.shape
+    ws = T.workspace(S, d, N, P, k, dt)
+    g = T.gate(x, w, P, k, want_logits=want_logits, ws=ws)
+    pen = torch.from_numpy(penalty.astype(np.float32)).cuda()
+    capd = torch.from_numpy(cap.astype(np.int32)).cuda()
+    l_topo = T.aux_loss(g["m"], g["c_expert"], pen, P, S) if S > 0 else None
+    l_aux = T.aux_loss(g["m"], g["c_expert"], None, P, S) if S > 0 else None
+    dsp = T.dispatch(x, g["topk_idx"], capd, N, P, ws=ws)
+    torch.cuda.synchronize()
+    K = int(dsp["expert_offset"][-1].item())
+    y = T.combine(dsp["send"], K, dsp["slot"], g["topk_w"], d=d)
+    torch.cuda.synchronize()
+    out = {
+        "logits": g["logits"].cpu().numpy() if want_logits else None,
+        "topk_idx": g["topk_idx"].cpu().numpy(), "topk_w": g["topk_w"].cpu().numpy(),
+        "m": g["m"].cpu().numpy(), "c_expert": g["c_expert"].cpu().numpy(), "c_device": g["c_device"].cpu().numpy(),
+        "l_topo": float(l_topo.item()) if l_topo is not None else None,
+        "l_aux": float(l_aux.item()) if l_aux is not None else None,
+        "slot": dsp["slot"].cpu().numpy(), "kept_expert": dsp["kept_expert"].cpu().numpy(),
+        "expert_offset": dsp["expert_offset"].cpu().numpy(), "send_count_dev": dsp["send_count_dev"].cpu().numpy(),
+        "K": K, "send_t": dsp["send"], "y": to_host(y, dt),
+    }
+    return out
+
+
+def full_parity(T, oracle, spec, x_np, w_np, penalty, cap, sample=None):
+    """All stages.  `sample` = token indices for the stages that are too slow on the CPU at full
+    size (scores, combine); None = every token."""
+    dt, N, P, k = spec["dtype"], spec["N"], spec["P"], spec["k"]
+    S, d = x_np.shape
+    g = gpu_path(T, spec, x_np, w_np, penalty, cap)
+    rows = np.arange(S) if sample is None else np.asarray(sample)
+
+    # A: scores
+    ref_lg = oracle.logits(np.ascontiguousarray(x_np[rows]), w_np, dt)
+    check_logits(g["logits"][rows], ref_lg, dt)
+
+    # B: routing from the GPU's own scores (cheap: every token)
+    ref = oracle.route_from_logits(g["logits"].astype(np.float64), k, P, penalty, cap)
+    check_routing(T, oracle, g, ref, N, k)
+    assert g["K"] == ref["K"]
+
+    # C: send buffer (every row)
+    send = to_host(g["send_t"][: g["K"]], dt)
+    ref_send = oracle.scatter(x_np, dt, ref["slot"], ref["K"])
+    np.testing.assert_array_equal(send, ref_send)
+
+    # D: combine on the sampled tokens, identity expert, GPU weights
+    slot_s = ref["slot"][rows]
+    used = np.unique(slot_s[slot_s >= 0])
+    remap = -np.ones(max(ref["K"], 1), dtype=np.int32)
+    remap[used] = np.arange(len(used), dtype=np.int32)
+    slot_sub = np.where(slot_s >= 0, remap[np.maximum(slot_s, 0)], -1).astype(np.int32)
+    recv_sub = np.ascontiguousarray(ref_send[used]) if len(used) else np.zeros((0, d), dtype=ref_send.dtype)
+    wg = g["topk_w"][rows].astype(np.float64)
+    y_exact, y_ref = oracle.combine(recv_sub if len(used) else np.zeros((1, d), dtype=ref_send.dtype),
+                                    dt, slot_sub, wg)
+    xv = np.abs(W.storage_to_f64(np.ascontiguousarray(x_np[rows]), dt))
+    mag = (np.where(slot_s >= 0, np.abs(wg), 0.0).sum(axis=1))[:, None] * xv
+    check_combine(g["y"][rows], y_exact, y_ref, mag, dt, k)
+
+    # E: end to end, oracle on its own scores (needs all tokens' scores: only when not sampled)
+    if sample is None and S > 0:
+        own = oracle.route_from_logits(ref_lg, k, P, penalty, cap)
+        tol = 1e-3 if dt == W.BF16 else 1e-5
+        assert g["l_topo"] == pytest.approx(own["l_topo"], rel=tol)
+        assert g["l_aux"] == pytest.approx(own["l_aux"], rel=tol)
+    return g, ref
+
+
+def spec_of(wl):
+    return {"dtype": wl.dtype, "N": wl.N, "P": wl.P, "k": wl.k}
+
+
+# ---------------------------------------------------------------------------
+# the five configurations, both capacity modes
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("name", ["tiny", "small", "gpt_moe", "skewed"])
+@pytest.mark.parametrize("cap_mode", [0, 1])
+def test_config_parity(T, oracle, name, cap_mode):
+    wl = W.WORKLOADS[name]
+    oracle.set_threads(oracle.max_threads())
+    inp = W.make_inputs(wl)
+    beta, level = W.topology(wl)
+    rank = 0 if cap_mode == 0 else wl.P // 2 + 1
+    c_hat, pen, cap = T.tamoe_topo_pattern(beta, level, wl.P, wl.N, rank, wl.k, wl.S, wl.capacity_factor, cap_mode)
+    g, ref = full_parity(T, oracle, spec_of(wl), inp["x"], inp["w"], pen.astype(np.float64), cap)
+    if name == "skewed":
+        assert ref["K"] < wl.k * wl.S * 0.6, "the skewed configuration must drop a large share of the pairs"
+        share = ref["c_expert"] / ref["c_expert"].sum()
+        assert share[0] > 0.2 and share[0] > 5 * share[16]
+
+
+def test_large_config_parity_sampled(T, oracle):
+    """Full size, the launch configuration the benchmark times.  Scores and combine are checked
+    on a sample of tokens; selection, slots and the send buffer on every token."""
+    wl = W.WORKLOADS["large"]
+    oracle.set_threads(oracle.max_threads())
+    inp = W.make_inputs(wl)
+    beta, level = W.topology(wl)
+    c_hat, pen, cap = T.tamoe_topo_pattern(beta, level, wl.P, wl.N, 0, wl.k, wl.S, wl.capacity_factor, 0)
+    rng = np.random.default_rng(99)
+    sample = np.sort(np.concatenate([rng.choice(wl.S, 1500, replace=False), [0, 31, 32, 127, 128, wl.S - 1]]))
+    sample = np.unique(sample)
+    full_parity(T, oracle, spec_of(wl), inp["x"], inp["w"], pen.astype(np.float64), cap, sample=sample)
+
+
+# ---------------------------------------------------------------------------
+# ragged shapes, small and odd sizes, limits
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("dtype,S,d,N,P,k,cf", [
+    (W.BF16, 1, 8, 1, 1, 1, 1.0),          # smallest everything
+    (W.BF16, 33, 72, 5, 5, 2, 1.0),        # ragged tile, K tail, odd N
+    (W.BF16, 129, 200, 48, 16, 3, 0.5),    # N not a multiple of 32, E = 3
+    (W.BF16, 1000, 64, 128, 64, 8, 1.0),   # k at the limit, N at the limit
+    (W.BF16, 2500, 264, 96, 8, 2, 2.0),    # several count tiles, ragged end
+    (W.BF16, 70000, 16, 32, 4, 1, 1.1),    # many tokens, tiny rows
+    (W.F32, 1, 4, 2, 1, 2, 1.0),
+    (W.F32, 77, 36, 33, 11, 4, 0.7),
+    (W.F32, 1500, 100, 128, 2, 2, 1.0),
+    (W.F32, 300, 1024, 64, 64, 1, 1.0),
+])
+def test_odd_shapes(T, oracle, dtype, S, d, N, P, k, cf):
+    oracle.set_threads(oracle.max_threads())
+    rng = np.random.default_rng(S * 31 + d)
+    x = W.to_storage(rng.standard_normal((S, d)).astype(np.float32), dtype)
+    w = W.to_storage((rng.standard_normal((N, d)) / math.sqrt(d)).astype(np.float32), dtype)
+    beta = rng.uniform(1.0, 9.0, size=(P, P))
+    rank = P // 2
+    c_hat, pen, cap = T.tamoe_topo_pattern(beta, None, P, N, rank, k, S, cf, 1)
+    full_parity(T, oracle, {"dtype": dtype, "N": N, "P": P, "k": k}, x, w, pen.astype(np.float64), cap)
+
+
+def test_empty_input(T):
+    N, P, k, d = 8, 4, 2, 64
+    x = torch.empty((0, d), dtype=torch.bfloat16, device="cuda")
+    w = torch.zeros((N, d), dtype=torch.bfloat16, device="cuda")
+    g = T.gate(x, w, P, k)
+    cap = torch.full((N,), 5, dtype=torch.int32, device="cuda")
+    dsp = T.dispatch(x, g["topk_idx"], cap, N, P)
+    y = T.combine(dsp["send"], 0, dsp["slot"], g["topk_w"], d=d)
+    torch.cuda.synchronize()
+    assert g["c_expert"].sum().item() == 0 and g["c_device"].sum().item() == 0
+    assert (g["m"] == 0).all()
+    assert dsp["kept_expert"].sum().item() == 0 and (dsp["expert_offset"] == 0).all()
+    assert dsp["send_count_dev"].sum().item() == 0 and y.shape == (0, d)
+
+
+# ---------------------------------------------------------------------------
+# selection stage fed given scores: ties, extreme values
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("S,N,P,k,ties", [(1000, 16, 4, 3, True), (777, 64, 8, 2, True), (513, 128, 1, 8, True),
+                                          (4000, 8, 8, 1, False), (100, 40, 10, 5, False)])
+def test_select_on_given_scores(T, oracle, S, N, P, k, ties):
+    lg = W.random_logits(S + N, S, N, ties=ties)
+    if not ties:
+        lg = lg * np.float32(20.0)            # wide dynamic range: exp underflows for most experts
+    out = T.select(torch.from_numpy(lg).cuda(), P, k)
+    torch.cuda.synchronize()
+    pen = np.full(N, 1.0 / N)
+    ref = oracle.route_from_logits(lg.astype(np.float64), k, P, pen, np.full(N, S * k, dtype=np.int32))
+    np.testing.assert_array_equal(out["topk_idx"].cpu().numpy(), ref["topk_idx"])
+    np.testing.assert_allclose(out["topk_w"].cpu().numpy(), ref["topk_w"], rtol=1e-5, atol=1e-37)
+    np.testing.assert_allclose(out["m"].cpu().numpy(), ref["m"], rtol=1e-5, atol=1e-12)
+    np.testing.assert_array_equal(out["c_expert"].cpu().numpy(), ref["c_expert"])
+    np.testing.assert_array_equal(out["c_device"].cpu().numpy(), ref["c_device"])
+
+
+def test_all_equal_scores_pick_the_first_k(T):
+    lg = torch.zeros((70, 12), dtype=torch.float32, device="cuda")
+    out = T.select(lg, 3, 4)
+    torch.cuda.synchronize()
+    assert (out["topk_idx"].cpu() == torch.arange(4, dtype=torch.int32)[None, :]).all()
+    np.testing.assert_allclose(out["topk_w"].cpu().numpy(), 1.0 / 12, rtol=1e-6)
+
+
+# ---------------------------------------------------------------------------
+# dispatch fed given routing: capacities, skew, bad indices; combine on foreign rows
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("S,N,P,k,capv,skew", [
+    (5000, 16, 4, 2, 300, 1.5), (3000, 64, 64, 1, 0, 0.0), (2049, 128, 64, 4, 10 ** 6, 0.5),
+    (100, 8, 2, 8, 37, 0.0), (1025, 4, 4, 2, 1, 3.0)])
+def test_dispatch_on_given_routing(T, oracle, S, N, P, k, capv, skew):
+    d = 32
+    idx = W.random_routing(S + k, S, N, k, skew)
+    cap = np.full(N, capv, dtype=np.int32)
+    if capv > 0:
+        cap[1::3] += 5
+    rng = np.random.default_rng(1)
+    x = W.to_storage(rng.standard_normal((S, d)).astype(np.float32), W.BF16)
+    dsp = T.dispatch(to_dev(x, W.BF16), torch.from_numpy(idx).cuda(), torch.from_numpy(cap).cuda(), N, P)
+    torch.cuda.synchronize()
+    slot, kept, off, scd, K = oracle.slots(idx, cap, P)
+    np.testing.assert_array_equal(dsp["slot"].cpu().numpy(), slot)
+    np.testing.assert_array_equal(dsp["kept_expert"].cpu().numpy(), kept)
+    np.testing.assert_array_equal(dsp["expert_offset"].cpu().numpy(), off)
+    np.testing.assert_array_equal(dsp["send_count_dev"].cpu().numpy(), scd)
+    np.testing.assert_array_equal(to_host(dsp["send"][:K], W.BF16), oracle.scatter(x, W.BF16, slot, K))
+
+
+def test_dispatch_treats_out_of_range_experts_as_dropped(T, oracle):
+    S, N, P, k, d = 600, 8, 4, 2, 16
+    idx = W.random_routing(5, S, N, k)
+    bad = idx.copy()
+    bad[::7, 1] = N + 3
+    bad[3::11, 0] = -2
+    cap = np.full(N, 50, dtype=np.int32)
+    x = np.arange(S * d, dtype=np.float32).reshape(S, d)
+    dsp = T.dispatch(torch.from_numpy(x).cuda(), torch.from_numpy(bad).cuda(), torch.from_numpy(cap).cuda(), N, P)
+    torch.cuda.synchronize()
+    slot = dsp["slot"].cpu().numpy()
+    invalid = (bad < 0) | (bad >= N)
+    assert (slot[invalid] == -1).all()
+    # the valid pairs are ranked as if the bad ones were absent: oracle on a routing where the bad
+    # pairs point at an extra expert with zero capacity
+    patched = np.where(invalid, N, bad).astype(np.int32)
+    oslot, okept, ooff, _, K = oracle.slots(patched, np.concatenate([cap, [0]]).astype(np.int32), 1)
+    np.testing.assert_array_equal(slot, oslot)
+    np.testing.assert_array_equal(dsp["kept_expert"].cpu().numpy(), okept[:N])
+    np.testing.assert_array_equal(to_host(dsp["send"][:K], W.F32), oracle.scatter(x, W.F32, oslot, K))
+
+
+@pytest.mark.parametrize("dtype,k", [(W.BF16, 2), (W.BF16, 1), (W.F32, 3), (W.BF16, 5)])
+def test_combine_on_foreign_rows(T, oracle, dtype, k):
+    """recv is not the send buffer: catches a combine that reads x or the wrong row."""
+    S, d, K = 3000, 136, 4500
+    rng = np.random.default_rng(k)
+    recv = W.to_storage(rng.standard_normal((K, d)).astype(np.float32), dtype)
+    slot = rng.integers(-1, K, size=(S, k)).astype(np.int32)
+    slot[5] = -1
+    slot[6, 0] = K + 10            # beyond K_rows: ignored like a dropped pair
+    wgt = rng.uniform(0.0, 1.0, size=(S, k)).astype(np.float32)
+    y = T.combine(to_dev(recv, dtype), K, torch.from_numpy(slot).cuda(), torch.from_numpy(wgt).cuda())
+    torch.cuda.synchronize()
+    oslot = np.where(slot >= K, -1, slot).astype(np.int32)
+    y_exact, y_ref = oracle.combine(recv, dtype, oslot, wgt.astype(np.float64))
+    rv = np.abs(W.storage_to_f64(recv, dtype))
+    mag = np.zeros((S, d))
+    for j in range(k):
+        ok = oslot[:, j] >= 0
+        mag[ok] += wgt[ok, j:j + 1].astype(np.float64) * rv[oslot[ok, j]]
+    check_combine(to_host(y, dtype), y_exact, y_ref, mag, dtype, k)
+    assert (W.storage_to_f64(to_host(y, dtype), dtype)[5] == 0).all()
+
+
+# ---------------------------------------------------------------------------
+# determinism, optional outputs, losses
+# ---------------------------------------------------------------------------
+def test_runs_are_bitwise_repeatable_and_logits_are_optional(T):
+    wl = W.WORKLOADS["small"]
+    inp = W.make_inputs(wl)
+    beta, level = W.topology(wl)
+    _, pen, cap = T.tamoe_topo_pattern(beta, level, wl.P, wl.N, 0, wl.k, wl.S, wl.capacity_factor, 0)
+    a = gpu_path(T, spec_of(wl), inp["x"], inp["w"], pen, cap, want_logits=True)
+    b = gpu_path(T, spec_of(wl), inp["x"], inp["w"], pen, cap, want_logits=False)
+    for key in ("topk_idx", "topk_w", "m", "c_expert", "c_device", "slot", "kept_expert", "expert_offset",
+                "send_count_dev", "y"):
+        np.testing.assert_array_equal(a[key], b[key], err_msg=key)
+    assert a["l_topo"] == b["l_topo"] and a["K"] == b["K"]
+    assert torch.equal(a["send_t"][: a["K"]].view(torch.int16), b["send_t"][: b["K"]].view(torch.int16))
+
+
+def test_aux_loss_closed_forms_on_device(T):
+    """Uniform routing: l_topo = k/E for any penalty that sums to one; l_aux = k/N."""
+    N, P, k, S = 64, 32, 2, 4096
+    m = torch.full((N,), 1.0 / N, device="cuda")
+    c = torch.full((N,), k * S // N, dtype=torch.int32, device="cuda")
+    beta, level = W.two_tier_topology(4, 8, 6.0)
+    _, pen, _ = T.tamoe_topo_pattern(beta, level, P, N, 5, k, S, 1.0, 0)
+    lt = T.aux_loss(m, c, torch.from_numpy(pen).cuda(), P, S).item()
+    la = T.aux_loss(m, c, None, P, S).item()
+    assert lt == pytest.approx(k / (N // P), rel=1e-5)
+    assert la == pytest.approx(k / N, rel=1e-5)
