@@ -1,0 +1,242 @@
+#!/usr/bin/env python3
+"""Benchmark of the TA-MoE hot path on one MI355X.
+
+A step is one pass of the whole path over one batch of synthetic tokens that are already in
+HBM: tamoe_gate -> tamoe_aux_loss -> tamoe_dispatch -> tamoe_combine (identity expert: the
+combine reads the send buffer).  The metric is routed tokens per second.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload large] [--cap-mode 0]
+
+Prints one JSON line.  Besides the contract fields it carries
+  roofline     achieved algorithmic HBM GB/s of the longest-running kernel against 8 TB/s,
+               from HIP events recorded around every kernel launch inside the timed region;
+  kernels      the same for every kernel of the step;
+  cpu_baseline the CPU oracle timed on the host cores on a bounded sample of the workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0     # MI355X HBM3E, vendor figure
+TRAFFIC_FILE = os.path.join(ROOT, "profiles", "hbm_traffic.txt")
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="large")
+    ap.add_argument("--cap-mode", type=int, default=0, help="0 uniform capacity, 1 proportional to the target pattern")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target CPU time of the oracle sample")
+    return ap.parse_args()
+
+
+def measured_traffic(workload: str, kernel: str):
+    """HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE + WRITE_SIZE), as recorded in
+    profiles/hbm_traffic.txt: lines `<workload> <kernel> <bytes>`.  None if not recorded."""
+    try:
+        with open(TRAFFIC_FILE) as f:
+            for line in f:
+                parts = line.split()
+                if len(parts) >= 3 and not line.startswith("#") and parts[0] == workload and parts[1] == kernel:
+                    return float(parts[2])
+    except OSError:
+        pass
+    return None
+
+
+def cpu_baseline(wl, W, seconds: float):
+    """The oracle, as it stands, on a bounded sample of the same workload."""
+    import oracle
+
+    threads = int(os.environ.get("OMP_NUM_THREADS", "0")) or min(16, os.cpu_count() or 1)
+    threads = max(1, min(threads, oracle.max_threads()))
+    oracle.set_threads(threads)
+    beta, level = W.topology(wl)
+
+    def run(S):
+        inp = W.make_inputs(wl, S=S)
+        t0 = time.perf_counter()
+        c_hat, p, cap = oracle.setup(beta, level, wl.N, wl.rank, wl.k, S, wl.capacity_factor, 0)
+        lg = oracle.logits(inp["x"], inp["w"], wl.dtype)
+        r = oracle.route_from_logits(lg, wl.k, wl.P, p, cap)
+        send = oracle.scatter(inp["x"], wl.dtype, r["slot"], r["K"])
+        oracle.combine(send, wl.dtype, r["slot"], r["topk_w"], want_exact=False, want_rounded=True)
+        return time.perf_counter() - t0
+
+    probe_S = min(wl.S, 256)
+    t_probe = run(probe_S)
+    S = int(min(wl.S, max(probe_S, seconds / max(t_probe, 1e-6) * probe_S)))
+    S = max(64, S // 64 * 64) if wl.S >= 64 else wl.S
+    t = run(S)
+    return {"value": S / t, "unit": "tokens/s", "cores": threads, "kind": "oracle",
+            "sample": f"first-draw sample of {S} of {wl.S} tokens of workload {wl.name}, whole path "
+                      f"(setup, scores, softmax, top-k, counts, losses, slots, scatter, combine), {t:.2f} s"}
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only; the exchange between devices is out of scope "
+              "(--gpus must be 1)", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    import paper_2302_09915_amd as T
+    import tamoe_workloads as W
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    T.lib()
+    wl = W.WORKLOADS[args.workload]
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+
+    inp = W.make_inputs(wl)
+    beta, level = W.topology(wl)
+    c_hat, pen, cap = T.tamoe_topo_pattern(beta, level, wl.P, wl.N, wl.rank, wl.k, wl.S, wl.capacity_factor,
+                                           args.cap_mode)
+
+    def up(a):
+        t = torch.from_numpy(a)
+        if wl.dtype == W.BF16:
+            t = t.view(torch.int16).view(torch.bfloat16)
+        return t.to(dev)
+
+    x, w = up(inp["x"]), up(inp["w"])
+    del inp
+    S, d, N, P, k = wl.S, wl.d, wl.N, wl.P, wl.k
+    b = wl.elem_bytes
+    pen_d = torch.from_numpy(pen).to(dev)
+    cap_d = torch.from_numpy(cap).to(dev)
+    ws = T.workspace(S, d, N, P, k, wl.dtype, dev)
+    i32, f32 = torch.int32, torch.float32
+    topk_idx = torch.empty((S, k), dtype=i32, device=dev)
+    topk_w = torch.empty((S, k), dtype=f32, device=dev)
+    m = torch.empty((N,), dtype=f32, device=dev)
+    c_expert = torch.empty((N,), dtype=i32, device=dev)
+    c_device = torch.empty((P,), dtype=i32, device=dev)
+    loss = torch.empty((1,), dtype=f32, device=dev)
+    send = torch.empty((S * k, d), dtype=x.dtype, device=dev)
+    slot = torch.empty((S, k), dtype=i32, device=dev)
+    kept = torch.empty((N,), dtype=i32, device=dev)
+    off = torch.empty((N + 1,), dtype=i32, device=dev)
+    scd = torch.empty((P,), dtype=i32, device=dev)
+    y = torch.empty((S, d), dtype=x.dtype, device=dev)
+    stream = torch.cuda.current_stream()
+
+    def step():
+        T.tamoe_gate(x, w, P, k, None, topk_idx, topk_w, m, c_expert, c_device, ws, stream)
+        T.tamoe_aux_loss(m, c_expert, pen_d, P, S, loss, stream)
+        T.tamoe_dispatch(x, topk_idx, cap_d, N, P, send, slot, kept, off, scd, ws, stream)
+        # identity expert: the rows come back as they were sent; S*k bounds the row count
+        T.tamoe_combine(send, S * k, slot, topk_w, y, stream)
+
+    for _ in range(max(args.warmup, 0)):
+        step()
+    torch.cuda.synchronize()
+
+    # yardstick, outside the timed region: a plain copy of x into y (same size)
+    T.tamoe_trace_start(16)
+    for _ in range(5):
+        T.tamoe_copy_probe(x, y, stream)
+    n_rec = T.tamoe_trace_stop()
+    copy_us = float(np.median([T.tamoe_trace_get(i)[1] for i in range(n_rec)])) * 1e3
+    copy_gbs = 2.0 * S * d * b / (copy_us * 1e-6) / 1e9
+
+    launches_per_step = 8
+    T.tamoe_trace_start(launches_per_step * args.steps)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    n_rec = T.tamoe_trace_stop()
+    per_kernel = {}
+    for i in range(n_rec):
+        name, ms = T.tamoe_trace_get(i)
+        per_kernel.setdefault(name, []).append(ms)
+    T.tamoe_trace_clear()
+
+    ms_per_step = elapsed * 1e3 / args.steps
+    tokens_per_s = S * args.steps / elapsed
+
+    # realised routing (for the algorithmic byte counts)
+    K = int(off[-1].item())
+    live_tokens = int((slot >= 0).any(dim=1).sum().item())
+    row = d * b
+    algo_bytes = {
+        "gate_bf16_kernel": S * row + N * row + S * k * 8,
+        "gate_gemm_f32_kernel": S * row + N * row + S * N * 4,
+        "select_kernel": S * N * 4 + S * k * 8,
+        "dispatch_scatter_kernel": live_tokens * row + K * row + S * k * 8,
+        "combine_kernel": K * row + S * row + S * k * 8,
+    }
+    kernels = []
+    for name, ts in per_kernel.items():
+        avg_ms = float(np.mean(ts))
+        entry = {"kernel": name, "launches": len(ts), "avg_us": round(avg_ms * 1e3, 2)}
+        if name in algo_bytes:
+            entry["algo_bytes"] = int(algo_bytes[name])
+            entry["achieved_GBs"] = round(algo_bytes[name] / (avg_ms * 1e-3) / 1e9, 1)
+            entry["frac_of_hbm_peak"] = round(entry["achieved_GBs"] / HBM_PEAK_GBS, 4)
+        kernels.append(entry)
+    kernels.sort(key=lambda e: -e["avg_us"])
+    dom = next((e for e in kernels if "algo_bytes" in e), None)
+    roofline = None
+    if dom is not None:
+        roofline = {"kernel": dom["kernel"], "bound": "hbm", "achieved": dom["achieved_GBs"], "peak": HBM_PEAK_GBS,
+                    "unit": "GB/s", "frac": dom["frac_of_hbm_peak"],
+                    "traffic": measured_traffic(wl.name, dom["kernel"]),
+                    "algo_bytes_per_launch": dom["algo_bytes"], "avg_launch_us": dom["avg_us"]}
+
+    total_algo = algo_bytes["gate_bf16_kernel" if wl.dtype == W.BF16 else "gate_gemm_f32_kernel"] \
+        + algo_bytes["dispatch_scatter_kernel"] + algo_bytes["combine_kernel"]
+    result = {
+        "metric": "routed tokens/sec (gate+aux_loss+dispatch+combine), 1 GPU",
+        "value": round(tokens_per_s, 1),
+        "unit": "tokens/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16" if wl.dtype == W.BF16 else "f32",
+        "data": "synthetic",
+        "config": {"workload": wl.name, "S": S, "d": d, "N": N, "k": k, "P": P, "E": wl.E,
+                   "capacity_factor": wl.capacity_factor, "cap_mode": args.cap_mode,
+                   "topology": f"{wl.nodes}x{wl.devs_per_node} ratio {wl.bw_ratio:g}:1", "rank": wl.rank,
+                   "kept_rows_K": K, "tokens_with_a_kept_choice": live_tokens,
+                   "drop_rate": round(1.0 - K / (S * k), 4)},
+        "path_algo_bytes_per_step": int(total_algo),
+        "path_achieved_GBs": round(total_algo / (ms_per_step * 1e-3) / 1e9, 1),
+        "roofline": roofline,
+        "copy_probe": {"bytes_moved": int(2 * S * d * b), "median_us": round(copy_us, 2),
+                       "GBs": round(copy_gbs, 1), "frac_of_hbm_peak": round(copy_gbs / HBM_PEAK_GBS, 4)},
+        "kernels": kernels,
+        "l_topo": float(loss.item()),
+    }
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(wl, W, args.cpu_seconds)
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

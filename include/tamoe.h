@@ -183,6 +183,15 @@ int tamoe_trace_stop(void);
 int tamoe_trace_get(int i, char* name, size_t name_len, float* ms);
 int tamoe_trace_clear(void);
 
+/*
+ * Bandwidth yardstick for benchmarks (not a step of the path): a plain copy of `bytes` bytes
+ * (a multiple of 16) from src to dst, both device, 16-byte aligned, not overlapping, with one
+ * 16-byte load and store per lane.  It moves exactly 2*bytes through HBM, so its duration gives
+ * the bandwidth a simple streaming kernel reaches on the machine, and hardware byte counters
+ * read for it calibrate the same counters read for the kernels of the path.
+ */
+int tamoe_copy_probe(const void* src, void* dst, size_t bytes, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -32,7 +32,7 @@ OK, INVALID_ARG, UNSUPPORTED, WORKSPACE_TOO_SMALL, HIP_ERROR = 0, 1, 2, 3, 4
 EXPORTS = (
     "tamoe_version", "tamoe_last_error", "tamoe_topo_pattern", "tamoe_workspace_bytes",
     "tamoe_gate", "tamoe_select", "tamoe_aux_loss", "tamoe_dispatch", "tamoe_combine",
-    "tamoe_trace_start", "tamoe_trace_stop", "tamoe_trace_get", "tamoe_trace_clear",
+    "tamoe_trace_start", "tamoe_trace_stop", "tamoe_trace_get", "tamoe_trace_clear", "tamoe_copy_probe",
 )
 
 
@@ -81,6 +81,8 @@ def lib() -> ctypes.CDLL:
     L.tamoe_trace_get.argtypes = [i32, ctypes.c_char_p, sz, ctypes.POINTER(ctypes.c_float)]
     L.tamoe_trace_clear.restype = i32
     L.tamoe_trace_clear.argtypes = []
+    L.tamoe_copy_probe.restype = i32
+    L.tamoe_copy_probe.argtypes = [vp, vp, sz, vp]
     _lib = L
     return L
 
@@ -233,6 +235,13 @@ def tamoe_trace_get(i: int):
 
 def tamoe_trace_clear() -> None:
     _check(lib().tamoe_trace_clear())
+
+
+def tamoe_copy_probe(src, dst, stream=None) -> None:
+    nbytes = src.numel() * src.element_size()
+    if dst.numel() * dst.element_size() < nbytes:
+        raise TamoeError(INVALID_ARG, "dst is smaller than src")
+    _check(lib().tamoe_copy_probe(_dev(src, None, "src"), _dev(dst, None, "dst"), nbytes, _stream(stream)))
 
 
 # ---- allocating helpers -------------------------------------------------------------------

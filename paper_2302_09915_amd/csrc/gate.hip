@@ -17,6 +17,7 @@
 // Determinism: probability sums are reduced in a fixed tree (lanes, wavefronts, workgroups);
 // counts are integers.  A second small kernel folds the per-workgroup partials.
 #include <climits>
+#include <type_traits>
 
 #include "internal.h"
 
@@ -149,16 +150,20 @@ __device__ __forceinline__ void store_block_partials(const float (*m_w)[NB * 32]
     }
 }
 
-template <int NB, int WAVES>
+// KTAIL: d is not a multiple of the 64-element K chunk (the last chunk is partly out of range).
+template <int NB, int WAVES, bool KTAIL>
 __global__ __launch_bounds__(WAVES * 64) void gate_bf16_kernel(
     const uint16_t* __restrict__ x, const uint16_t* __restrict__ w, int64_t S, int d, int N, int k,
     float* __restrict__ logits, int32_t* __restrict__ topk_idx, float* __restrict__ topk_w,
     float* __restrict__ m_part, int32_t* __restrict__ c_part, int n_blocks) {
     constexpr int T = WAVES * 64;
-    constexpr int ROWS = NB * 32;
-    constexpr int UNITS = ROWS * 8 / T;  // 16-byte pieces of the W chunk per thread
-    static_assert(ROWS * 8 % T == 0, "W chunk must split evenly over the threads");
+    constexpr int ROWS = NB * 32;        // expert rows of the W tile
+    constexpr int TOK = WAVES * 32;      // token rows of the x tile
+    constexpr int WU = ROWS * 8 / T;     // 16-byte pieces of the W chunk per thread
+    constexpr int XU = TOK * 8 / T;      // 16-byte pieces of the x chunk per thread (= 4)
+    static_assert(ROWS * 8 % T == 0 && XU == 4, "tiles must split evenly over the threads");
     __shared__ __attribute__((aligned(16))) unsigned char w_lds[2][ROWS * kLdsRow];
+    __shared__ __attribute__((aligned(16))) unsigned char x_lds[2][TOK * kLdsRow];
     __shared__ float m_w[WAVES][ROWS];
     __shared__ int32_t hist[ROWS];
 
@@ -167,9 +172,9 @@ __global__ __launch_bounds__(WAVES * 64) void gate_bf16_kernel(
     const int wave = tid >> 6;
     const int r = lane & 31;
     const int half = lane >> 5;
-    const int64_t token = ((int64_t)blockIdx.x * WAVES + wave) * 32 + r;
+    const int64_t tile0 = (int64_t)blockIdx.x * TOK;
+    const int64_t token = tile0 + wave * 32 + r;
     const bool token_ok = token < S;
-    const uint16_t* xrow = x + (size_t)(token_ok ? token : 0) * d + half * 32;
 
     for (int e = tid; e < ROWS; e += T) hist[e] = 0;
     for (int q = tid; q < WAVES * ROWS; q += T) (&m_w[0][0])[q] = 0.f;
@@ -177,33 +182,67 @@ __global__ __launch_bounds__(WAVES * 64) void gate_bf16_kernel(
     const int n_chunks = (d + kKC - 1) / kKC;
     const vec16 zero = {0u, 0u, 0u, 0u};
 
-    vec16 wreg[UNITS];
-    vec16 xcur[4], xnext[4];
+    // Both tiles go global -> registers -> LDS -> MFMA operands.  Unit u of a thread is the
+    // 16-byte piece (unit & 7) of tile row (unit >> 3), unit = tid + u * T: eight consecutive
+    // lanes read one 128-byte line, so every global load instruction is fully coalesced (loading
+    // the x operand straight into its MFMA lane layout would touch 32 lines per instruction and
+    // stall the address unit on the L1 tag rate).
+    // Every load is unconditional so that the loop body is straight-line code and the loads of
+    // later chunks stay in flight across the MFMAs of the current one:
+    //  - a token row beyond S reads row S-1 (its results are discarded);
+    //  - an expert row beyond N reads row N-1 (its scores are masked before the selection);
+    //  - a chunk index beyond the last chunk reads the last chunk again (never consumed);
+    //  - with KTAIL, a 16-byte piece beyond d reads the last piece of the row; the W piece is then
+    //    replaced by zeros, so the finite x values it meets contribute nothing.
+    const uint16_t* wsrc[WU];
+    const uint16_t* xsrc[XU];
+    int lds_off_w[WU], lds_off_x[XU];
+#pragma unroll
+    for (int u = 0; u < WU; ++u) {
+        const int unit = tid + u * T;
+        const int row = unit >> 3;
+        wsrc[u] = w + (size_t)(row < N ? row : N - 1) * d + (unit & 7) * 8;
+        lds_off_w[u] = row * kLdsRow + (unit & 7) * 16;
+    }
+#pragma unroll
+    for (int u = 0; u < XU; ++u) {
+        const int unit = tid + u * T;
+        const int row = unit >> 3;
+        const int64_t t = tile0 + row;
+        xsrc[u] = x + (size_t)(t < S ? t : S - 1) * d + (unit & 7) * 8;
+        lds_off_x[u] = row * kLdsRow + (unit & 7) * 16;
+    }
+    const int piece = tid & 7;  // (unit & 7) is the same for every unit of a thread: T % 8 == 0
 
-    auto load_w = [&](int kc) {
+    auto load_w = [&](int kc, vec16 (&dst)[WU]) {
+        kc = kc < n_chunks ? kc : n_chunks - 1;
+        int k0 = kc * kKC;
+        bool in = true;
+        if constexpr (KTAIL) {
+            in = k0 + piece * 8 < d;
+            k0 = in ? k0 : d - 8 - piece * 8;
+        }
 #pragma unroll
-        for (int u = 0; u < UNITS; ++u) {
-            const int unit = tid + u * T;
-            const int row = unit >> 3, piece = unit & 7;
-            const int k0 = kc * kKC + piece * 8;
-            wreg[u] = (row < N && k0 < d) ? *reinterpret_cast<const vec16*>(w + (size_t)row * d + k0) : zero;
+        for (int u = 0; u < WU; ++u) {
+            const vec16 t = *reinterpret_cast<const vec16*>(wsrc[u] + k0);
+            dst[u] = (!KTAIL || in) ? t : zero;
         }
     };
-    auto store_w = [&](int buf) {
+    auto load_x = [&](int kc, vec16 (&dst)[XU]) {
+        kc = kc < n_chunks ? kc : n_chunks - 1;
+        int k0 = kc * kKC;
+        if constexpr (KTAIL) k0 = (k0 + piece * 8 < d) ? k0 : d - 8 - piece * 8;
 #pragma unroll
-        for (int u = 0; u < UNITS; ++u) {
-            const int unit = tid + u * T;
-            const int row = unit >> 3, piece = unit & 7;
-            *reinterpret_cast<vec16*>(&w_lds[buf][row * kLdsRow + piece * 16]) = wreg[u];
-        }
+        for (int u = 0; u < XU; ++u)
+            dst[u] = __builtin_nontemporal_load(reinterpret_cast<const vec16*>(xsrc[u] + k0));
     };
-    auto load_x = [&](int kc, vec16 (&dst)[4]) {
+    auto store_w = [&](const vec16 (&src)[WU], int buf) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int k0 = kc * kKC + half * 32 + i * 8;
-            dst[i] = (token_ok && k0 < d) ? __builtin_nontemporal_load(reinterpret_cast<const vec16*>(xrow + kc * kKC + i * 8))
-                                          : zero;
-        }
+        for (int u = 0; u < WU; ++u) *reinterpret_cast<vec16*>(&w_lds[buf][lds_off_w[u]]) = src[u];
+    };
+    auto store_x = [&](const vec16 (&src)[XU], int buf) {
+#pragma unroll
+        for (int u = 0; u < XU; ++u) *reinterpret_cast<vec16*>(&x_lds[buf][lds_off_x[u]]) = src[u];
     };
 
     f32x16 acc[NB];
@@ -212,34 +251,59 @@ __global__ __launch_bounds__(WAVES * 64) void gate_bf16_kernel(
 #pragma unroll
         for (int v = 0; v < 16; ++v) acc[nb][v] = 0.f;
 
-    load_w(0);
-    load_x(0, xcur);
-    store_w(0);
-    __syncthreads();
-
-    int buf = 0;
-    for (int kc = 0; kc < n_chunks; ++kc) {
-        const bool more = kc + 1 < n_chunks;
-        if (more) {
-            load_w(kc + 1);
-            load_x(kc + 1, xnext);
-        }
+    // MFMA operands of lane (r, half) for K step i of a chunk: the 16-byte piece 4*half + i of
+    // W row nb*32 + r (A) and of x row wave*32 + r (B).  Any order of the K pieces works as long
+    // as A and B use the same one.
+    auto compute = [&](int buf) {
         const unsigned char* wl = &w_lds[buf][r * kLdsRow + half * 64];
+        const unsigned char* xl = &x_lds[buf][(wave * 32 + r) * kLdsRow + half * 64];
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const bf16x8 b = __builtin_bit_cast(bf16x8, xcur[i]);
+            const bf16x8 b = *reinterpret_cast<const bf16x8*>(xl + i * 16);
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb) {
                 const bf16x8 a = *reinterpret_cast<const bf16x8*>(wl + nb * 32 * kLdsRow + i * 16);
                 acc[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[nb], 0, 0, 0);
             }
         }
-        if (more) store_w(buf ^ 1);
+    };
+
+    // Software pipeline.  Chunk c of x is requested four iterations before it is used (four
+    // register sets), chunk c of W two iterations before (two sets); both are copied to the LDS
+    // double buffer one iteration before use.  A wavefront keeps up to 16 KiB of x in flight.
+    vec16 wr[2][WU];
+    vec16 xr[4][XU];
+    auto stage = [&](int kc, auto U) {   // u = kc mod 4, a compile-time constant at each call
+        constexpr int u = decltype(U)::value;
+        load_w(kc + 2, wr[u & 1]);
+        load_x(kc + 4, xr[u]);
+        compute(u & 1);
+        store_w(wr[(u + 1) & 1], (u + 1) & 1);
+        store_x(xr[(u + 1) & 3], (u + 1) & 1);
         __syncthreads();
-#pragma unroll
-        for (int i = 0; i < 4; ++i) xcur[i] = xnext[i];
-        buf ^= 1;
+    };
+
+    load_w(0, wr[0]);
+    load_x(0, xr[0]);
+    load_w(1, wr[1]);
+    load_x(1, xr[1]);
+    load_x(2, xr[2]);
+    load_x(3, xr[3]);
+    store_w(wr[0], 0);
+    store_x(xr[0], 0);
+    __syncthreads();
+
+    const int n_groups = n_chunks >> 2;
+    for (int g = 0; g < n_groups; ++g) {
+        stage(4 * g + 0, std::integral_constant<int, 0>{});
+        stage(4 * g + 1, std::integral_constant<int, 1>{});
+        stage(4 * g + 2, std::integral_constant<int, 2>{});
+        stage(4 * g + 3, std::integral_constant<int, 3>{});
     }
+    const int rem = n_chunks & 3;  // uniform
+    if (rem > 0) stage(4 * n_groups + 0, std::integral_constant<int, 0>{});
+    if (rem > 1) stage(4 * n_groups + 1, std::integral_constant<int, 1>{});
+    if (rem > 2) stage(4 * n_groups + 2, std::integral_constant<int, 2>{});
 
     float sc[NB][16];
 #pragma unroll
@@ -372,16 +436,19 @@ static void launch_gate_bf16(int waves, int64_t blocks, hipStream_t st, const ui
                              int64_t S, int d, int N, int k, float* logits, int32_t* topk_idx, float* topk_w,
                              float* m_part, int32_t* c_part) {
     const dim3 grid((unsigned)blocks);
+    const bool ktail = d % kKC != 0;
     TraceScope tr("gate_bf16_kernel", st);
-    if (waves == 4)
-        gate_bf16_kernel<NB, 4><<<grid, dim3(256), 0, st>>>(x, w, S, d, N, k, logits, topk_idx, topk_w, m_part, c_part,
-                                                             (int)blocks);
-    else if (waves == 2)
-        gate_bf16_kernel<NB, 2><<<grid, dim3(128), 0, st>>>(x, w, S, d, N, k, logits, topk_idx, topk_w, m_part, c_part,
-                                                             (int)blocks);
-    else
-        gate_bf16_kernel<NB, 1><<<grid, dim3(64), 0, st>>>(x, w, S, d, N, k, logits, topk_idx, topk_w, m_part, c_part,
-                                                            (int)blocks);
+#define TAMOE_GATE_LAUNCH(WV, KT)                                                                                 \
+    gate_bf16_kernel<NB, WV, KT><<<grid, dim3(WV * 64), 0, st>>>(x, w, S, d, N, k, logits, topk_idx, topk_w, m_part, \
+                                                                  c_part, (int)blocks)
+    if (waves == 4) {
+        if (ktail) TAMOE_GATE_LAUNCH(4, true); else TAMOE_GATE_LAUNCH(4, false);
+    } else if (waves == 2) {
+        if (ktail) TAMOE_GATE_LAUNCH(2, true); else TAMOE_GATE_LAUNCH(2, false);
+    } else {
+        if (ktail) TAMOE_GATE_LAUNCH(1, true); else TAMOE_GATE_LAUNCH(1, false);
+    }
+#undef TAMOE_GATE_LAUNCH
 }
 
 static void launch_select(int64_t blocks, hipStream_t st, const float* logits, int64_t S, int N, int k,

@@ -88,10 +88,14 @@ def check_combine(y_gpu: np.ndarray, y_exact: np.ndarray, y_ref: np.ndarray, mag
     arith = 4.0 * k * 2.0 ** -24 * mag
     bound = 0.5 * ulp_of(y_exact, dtype) + arith + 2.0 ** -149
     assert (np.abs(yv - y_exact) <= bound).all()
-    flips = (y_gpu != y_ref)
-    # +0 / -0 are the same value
-    flips &= ~((W.storage_to_f64(y_ref, dtype) == 0) & (yv == 0))
-    assert flips.mean() <= 1e-3
+    if dtype == W.BF16:
+        # the storage ulp dwarfs the fp32 accumulation error: the once-rounded results agree except
+        # where the exact sum sits on a rounding boundary
+        flips = (y_gpu != y_ref)
+        flips &= ~((W.storage_to_f64(y_ref, dtype) == 0) & (yv == 0))      # +0 / -0 are the same value
+        assert flips.mean() <= 1e-3
+    else:
+        assert (np.abs(yv - y_exact) <= 1e-5 * np.maximum(np.abs(y_exact), mag)).all()
 
 
 def gpu_path(T, wl_like, x_np, w_np, penalty, cap, want_logits=True):
