@@ -158,7 +158,7 @@ def main():
     copy_us = float(np.median([T.tamoe_trace_get(i)[1] for i in range(n_rec)])) * 1e3
     copy_gbs = 2.0 * S * d * b / (copy_us * 1e-6) / 1e9
 
-    launches_per_step = 8
+    launches_per_step = 9
     T.tamoe_trace_start(launches_per_step * args.steps)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -184,7 +184,7 @@ def main():
         "gate_bf16_kernel": S * row + N * row + S * k * 8,
         "gate_gemm_f32_kernel": S * row + N * row + S * N * 4,
         "select_kernel": S * N * 4 + S * k * 8,
-        "dispatch_scatter_kernel": live_tokens * row + K * row + S * k * 8,
+        "dispatch_copy_kernel": live_tokens * row + K * row + S * k * 8,
         "combine_kernel": K * row + S * row + S * k * 8,
     }
     kernels = []
@@ -206,7 +206,7 @@ def main():
                     "algo_bytes_per_launch": dom["algo_bytes"], "avg_launch_us": dom["avg_us"]}
 
     total_algo = algo_bytes["gate_bf16_kernel" if wl.dtype == W.BF16 else "gate_gemm_f32_kernel"] \
-        + algo_bytes["dispatch_scatter_kernel"] + algo_bytes["combine_kernel"]
+        + algo_bytes["dispatch_copy_kernel"] + algo_bytes["combine_kernel"]
     result = {
         "metric": "routed tokens/sec (gate+aux_loss+dispatch+combine), 1 GPU",
         "value": round(tokens_per_s, 1),

@@ -1,16 +1,16 @@
 // tamoe_combine: y[t] = sum over the kept choices j of topk_w[t][j] * recv[slot[t][j]]
 // (paper Section 3.1: the layer output aggregates the computed results).
 //
-// One workgroup per row tile of 4..64 tokens.  The 16-byte chunks of the tile are laid out flat
-// over the threads; a thread gathers the same chunk of the (up to k) source rows, accumulates in
-// fp32 in ascending j with one fused multiply-add per term, rounds once to the storage type and
-// writes the chunk of y.  Bound by HBM: d*b bytes read per kept pair, d*b written per token.
+// The 16-byte chunks of y are laid out flat over the threads, a few per thread, no loop and no
+// LDS: a thread gathers the same chunk of the (up to k) source rows, accumulates in fp32 in
+// ascending j with one fused multiply-add per term, rounds once to the storage type and writes
+// the chunk of y.  Bound by HBM: d*b bytes read per kept pair, d*b written per token; the HBM
+// latency is covered by the number of independent wavefronts, as in a plain copy.
 #include "internal.h"
 
 namespace tamoe {
 
 constexpr int kThreads = 256;
-constexpr int kMaxRowTile = 64;
 
 template <int DT>
 struct Chunk;
@@ -55,85 +55,76 @@ struct Chunk<TAMOE_BF16> {
     }
 };
 
-// KK > 0: k is the compile-time constant KK (all source loads of a chunk are issued together);
-// KK == 0: any k up to TAMOE_MAX_K.
-template <int DT, int KK, int U>
-__global__ __launch_bounds__(kThreads) void combine_kernel(
-    const vec16* __restrict__ recv, int64_t K_rows, const int32_t* __restrict__ slot,
-    const float* __restrict__ topk_w, int64_t S, int k_arg, int row_tile, int cpr, vec16* __restrict__ y) {
-    __shared__ int32_t s_slot[kMaxRowTile * TAMOE_MAX_K];
-    __shared__ float s_w[kMaxRowTile * TAMOE_MAX_K];
+// KK > 0: k is the compile-time constant KK; KK == 0: any k up to TAMOE_MAX_K.
+// ROWU: a row is a multiple of 1 KiB, so the 64 chunks of a wavefront belong to one token and
+// its slots and weights are read once per wavefront through the scalar unit.
+template <int DT, int KK, int U, bool ROWU>
+__global__ __launch_bounds__(kThreads) void combine_kernel(const vec16* __restrict__ recv, int64_t K_rows,
+                                                           const int32_t* __restrict__ slot,
+                                                           const float* __restrict__ topk_w, int64_t total_chunks,
+                                                           int k_arg, int cpr, int shift, vec16* __restrict__ y) {
+    constexpr int KM = KK > 0 ? KK : TAMOE_MAX_K;
     const int k = KK > 0 ? KK : k_arg;
-    const int64_t t0 = (int64_t)blockIdx.x * row_tile;
-    const int rows = (int)min((int64_t)row_tile, S - t0);
-    for (int p = threadIdx.x; p < rows * k; p += kThreads) {
-        const int32_t s = slot[t0 * k + p];
-        s_slot[p] = (s >= 0 && (int64_t)s < K_rows) ? s : -1;
-        s_w[p] = topk_w[t0 * k + p];
-    }
-    __syncthreads();
-
-    const int total = rows * cpr;
-    vec16* dst = y + (size_t)t0 * cpr;
-    for (int base = 0; base < total; base += kThreads * U) {
-        if constexpr (KK > 0) {
-            vec16 v[U][KK];
-            int32_t sl[U][KK];
-            int row[U];
+    const int64_t base = (int64_t)blockIdx.x * (kThreads * U) + threadIdx.x;
+    vec16 v[U][KM];
+    float wgt[U][KM];
+    bool use[U][KM];
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int c = base + u * kThreads + threadIdx.x;
-                row[u] = -1;
-                if (c < total) {
-                    row[u] = c / cpr;
-                    const int col = c - row[u] * cpr;
+    for (int u = 0; u < U; ++u) {
+        const int64_t c = base + (int64_t)u * kThreads;
 #pragma unroll
-                    for (int j = 0; j < KK; ++j) {
-                        sl[u][j] = s_slot[row[u] * KK + j];
-                        if (sl[u][j] >= 0) v[u][j] = __builtin_nontemporal_load(recv + (size_t)sl[u][j] * cpr + col);
-                    }
+        for (int j = 0; j < KM; ++j) use[u][j] = false;
+        if (c < total_chunks) {
+            int t, col;
+            split_chunk(c, total_chunks, cpr, shift, t, col);
+            if (ROWU) t = __builtin_amdgcn_readfirstlane(t);
+#pragma unroll
+            for (int j = 0; j < KM; ++j) {
+                if (j < k) {
+                    const int32_t s = slot[(int64_t)t * k + j];
+                    wgt[u][j] = topk_w[(int64_t)t * k + j];
+                    use[u][j] = s >= 0 && (int64_t)s < K_rows;
+                    if (use[u][j]) v[u][j] = __builtin_nontemporal_load(recv + (size_t)s * cpr + col);
                 }
-            }
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                if (row[u] < 0) continue;
-                float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-                for (int j = 0; j < KK; ++j)
-                    if (sl[u][j] >= 0) Chunk<DT>::fma(acc, s_w[row[u] * KK + j], v[u][j]);
-                __builtin_nontemporal_store(Chunk<DT>::pack(acc), dst + base + u * kThreads + threadIdx.x);
-            }
-        } else {
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int c = base + u * kThreads + threadIdx.x;
-                if (c >= total) continue;
-                const int r = c / cpr;
-                const int col = c - r * cpr;
-                float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-                for (int j = 0; j < k; ++j) {
-                    const int32_t s = s_slot[r * k + j];
-                    if (s >= 0) Chunk<DT>::fma(acc, s_w[r * k + j], recv[(size_t)s * cpr + col]);
-                }
-                __builtin_nontemporal_store(Chunk<DT>::pack(acc), dst + c);
             }
         }
     }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        const int64_t c = base + (int64_t)u * kThreads;
+        if (c >= total_chunks) continue;
+        float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int j = 0; j < KM; ++j)
+            if (use[u][j]) Chunk<DT>::fma(acc, wgt[u][j], v[u][j]);
+        __builtin_nontemporal_store(Chunk<DT>::pack(acc), y + c);
+    }
+}
+
+template <int DT, int KK, int U>
+static void launch_combine_k(const void* recv, int64_t K_rows, const int32_t* slot, const float* topk_w, int64_t S,
+                             int k, int cpr, void* y, hipStream_t st) {
+    const int64_t total = S * (int64_t)cpr;
+    const dim3 grid((unsigned)ceil_div(total, kThreads * U)), block(kThreads);
+    const vec16* r = static_cast<const vec16*>(recv);
+    vec16* out = static_cast<vec16*>(y);
+    const int shift = pow2_shift(cpr);
+    if (cpr % 64 == 0)
+        combine_kernel<DT, KK, U, true><<<grid, block, 0, st>>>(r, K_rows, slot, topk_w, total, k, cpr, shift, out);
+    else
+        combine_kernel<DT, KK, U, false><<<grid, block, 0, st>>>(r, K_rows, slot, topk_w, total, k, cpr, shift, out);
 }
 
 template <int DT>
 static void launch_combine(const void* recv, int64_t K_rows, const int32_t* slot, const float* topk_w, int64_t S,
-                           int k, int rt, int cpr, void* y, hipStream_t st) {
-    const dim3 grid((unsigned)ceil_div(S, rt)), block(kThreads);
-    const vec16* r = static_cast<const vec16*>(recv);
-    vec16* out = static_cast<vec16*>(y);
+                           int k, int cpr, void* y, hipStream_t st) {
     TraceScope tr("combine_kernel", st);
     if (k == 1)
-        combine_kernel<DT, 1, 4><<<grid, block, 0, st>>>(r, K_rows, slot, topk_w, S, k, rt, cpr, out);
+        launch_combine_k<DT, 1, 2>(recv, K_rows, slot, topk_w, S, k, cpr, y, st);
     else if (k == 2)
-        combine_kernel<DT, 2, 2><<<grid, block, 0, st>>>(r, K_rows, slot, topk_w, S, k, rt, cpr, out);
+        launch_combine_k<DT, 2, 1>(recv, K_rows, slot, topk_w, S, k, cpr, y, st);
     else
-        combine_kernel<DT, 0, 2><<<grid, block, 0, st>>>(r, K_rows, slot, topk_w, S, k, rt, cpr, out);
+        launch_combine_k<DT, 0, 1>(recv, K_rows, slot, topk_w, S, k, cpr, y, st);
 }
 
 }  // namespace tamoe
@@ -155,15 +146,13 @@ extern "C" int tamoe_combine(const void* recv, int64_t K_rows, const int32_t* sl
     if ((rc = check_ptr(fn, "slot", slot, 4)) != TAMOE_OK) return rc;
     if ((rc = check_ptr(fn, "topk_w", topk_w, 4)) != TAMOE_OK) return rc;
     if ((rc = check_ptr(fn, "y", y, 16)) != TAMOE_OK) return rc;
-    const int row_bytes = d * elem_bytes(dtype);
-    const int cpr = row_bytes / 16;
-    if (cpr > 65536) return fail(TAMOE_UNSUPPORTED, "%s: rows longer than 1 MiB are not supported", fn);
-    const int rt = row_tile(S, row_bytes);
-    if (ceil_div(S, rt) > 0x7fffffff) return fail(TAMOE_UNSUPPORTED, "%s: too many row tiles", fn);
+    const int cpr = d * elem_bytes(dtype) / 16;  // 16-byte chunks per row
+    if (ceil_div(S * (int64_t)cpr, kThreads * 1) > 0x7fffffff)
+        return fail(TAMOE_UNSUPPORTED, "%s: y is too large for one launch", fn);
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (dtype == TAMOE_F32)
-        launch_combine<TAMOE_F32>(recv, K_rows, slot, topk_w, S, k, rt, cpr, y, st);
+        launch_combine<TAMOE_F32>(recv, K_rows, slot, topk_w, S, k, cpr, y, st);
     else
-        launch_combine<TAMOE_BF16>(recv, K_rows, slot, topk_w, S, k, rt, cpr, y, st);
+        launch_combine<TAMOE_BF16>(recv, K_rows, slot, topk_w, S, k, cpr, y, st);
     return check_launch(fn, "combine_kernel");
 }

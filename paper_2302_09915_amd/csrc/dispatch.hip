@@ -2,25 +2,27 @@
 // destination-grouped send buffer (paper Section 3.1: dispatched data [k*S, d], local capacity;
 // Section 4.1: one merged delivery per destination device; Section 4.3: variable chunk sizes).
 //
-// Three launches, no atomics on positions, so the result is the same on every run:
-//   1. dispatch_count_kernel   pairs per (choice j, count tile of 1024 tokens, expert)
-//   2. dispatch_scan_kernel    exclusive prefix of those counts in priority order (choice-major,
-//                              then token order), kept = min(count, cap), expert offsets,
-//                              rows per destination device
-//   3. dispatch_scatter_kernel one workgroup per row tile (4..64 tokens): recount the pairs of
-//                              the count tile that precede the row tile, rank the tile's own
-//                              pairs, write slot[], then stream the rows: each 16-byte chunk
-//                              of a kept token is read once and stored to each of its slots.
+// Four launches, no atomics on positions, so the result is the same on every run:
+//   1. dispatch_count_kernel  pairs per (choice j, count tile of 1024 tokens, expert)
+//   2. dispatch_scan_kernel   exclusive prefix of those counts in priority order (choice-major,
+//                             then token order), kept = min(count, cap), expert offsets, rows per
+//                             destination device
+//   3. dispatch_slot_kernel   one workgroup per 64 tokens: recount the pairs of the count tile
+//                             that precede them, rank the 64 tokens' own pairs, write slot[]
+//   4. dispatch_copy_kernel   streams the rows: each thread owns four 16-byte chunks of x, reads
+//                             a chunk once if its token has a kept choice and stores it to each
+//                             of the token's slots.  No loop and no LDS: like a plain copy, the
+//                             latency of HBM is covered by the number of independent wavefronts.
 //
-// The scatter is bound by HBM: it reads d*b bytes per token with a kept choice and writes d*b
-// bytes per kept pair.  Chunks of a tile are laid out flat over the workgroup's threads, so a
-// wavefront always touches 1 KiB of consecutive bytes of a row, whatever d is.
+// The copy is bound by HBM: it reads d*b bytes per token with a kept choice and writes d*b
+// bytes per kept pair.  Chunks are laid out flat over the threads, so a wavefront always touches
+// 1 KiB of consecutive bytes, whatever d is.
 #include "internal.h"
 
 namespace tamoe {
 
 constexpr int kThreads = 256;
-constexpr int kMaxRowTile = 64;
+constexpr int kSlotTile = 64;  // tokens per slot-assignment workgroup; divides kCountTile
 
 __global__ __launch_bounds__(kThreads) void dispatch_count_kernel(
     const int32_t* __restrict__ idx, int64_t S, int N, int k, int n_ct, int32_t* __restrict__ tile_count) {
@@ -95,25 +97,22 @@ __global__ __launch_bounds__(kScanThreads) void dispatch_scan_kernel(
     }
 }
 
-template <int U>
-__global__ __launch_bounds__(kThreads) void dispatch_scatter_kernel(
-    const vec16* __restrict__ x, const int32_t* __restrict__ idx, const int32_t* __restrict__ cap,
-    const int32_t* __restrict__ tile_base, const int32_t* __restrict__ expert_offset, int64_t S, int N,
-    int k, int n_ct, int row_tile, int cpr, vec16* __restrict__ send, int32_t* __restrict__ slot) {
+__global__ __launch_bounds__(kThreads) void dispatch_slot_kernel(
+    const int32_t* __restrict__ idx, const int32_t* __restrict__ cap, const int32_t* __restrict__ tile_base,
+    const int32_t* __restrict__ expert_offset, int64_t S, int N, int k, int n_ct, int32_t* __restrict__ slot) {
     __shared__ int32_t before[TAMOE_MAX_K * TAMOE_MAX_EXPERTS];
-    __shared__ int32_t s_idx[kMaxRowTile * TAMOE_MAX_K];
-    __shared__ int32_t s_slot[kMaxRowTile * TAMOE_MAX_K];
+    __shared__ int32_t s_idx[kSlotTile * TAMOE_MAX_K];
 
-    const int64_t t0 = (int64_t)blockIdx.x * row_tile;
+    const int64_t t0 = (int64_t)blockIdx.x * kSlotTile;
     const int ct = (int)(t0 / kCountTile);
     const int64_t tile_begin = (int64_t)ct * kCountTile;
-    const int rows = (int)min((int64_t)row_tile, S - t0);
+    const int rows = (int)min((int64_t)kSlotTile, S - t0);
     const int pairs = rows * k;
 
     for (int q = threadIdx.x; q < k * N; q += kThreads) before[q] = 0;
     for (int p = threadIdx.x; p < pairs; p += kThreads) s_idx[p] = idx[t0 * k + p];
     __syncthreads();
-    // pairs of this count tile that come before the row tile (same choice j)
+    // pairs of this count tile that come before these tokens (same choice j)
     for (int64_t p = tile_begin * k + threadIdx.x; p < t0 * k; p += kThreads) {
         const int e = idx[p];
         const int j = (int)(p % k);
@@ -129,39 +128,64 @@ __global__ __launch_bounds__(kThreads) void dispatch_scatter_kernel(
             for (int tt = 0; tt < tl; ++tt) pos += (s_idx[tt * k + j] == e) ? 1 : 0;
             if (pos < cap[e]) sl = expert_offset[e] + pos;
         }
-        s_slot[p] = sl;
         slot[t0 * k + p] = sl;
     }
-    __syncthreads();
+}
 
-    const int total = rows * cpr;  // 16-byte chunks in this tile (<= 64 rows * 2^16 chunks)
-    const vec16* src = x + (size_t)t0 * cpr;
-    for (int base = 0; base < total; base += kThreads * U) {
-        vec16 v[U];
-        int row[U], col[U];
-        bool live[U];
+// KK > 0: k is the compile-time constant KK; KK == 0: any k up to TAMOE_MAX_K.
+// ROWU: a row is a multiple of 1 KiB, so the 64 chunks of a wavefront belong to one token and
+// its slots are read once per wavefront through the scalar unit.
+// `shift` >= 0: cpr == 1 << shift, and the (token, column) split of a chunk index is a shift and a
+// mask; otherwise it is a division (32-bit when the tensor has fewer than 2^32 chunks).
+template <int KK, int U, bool ROWU>
+__global__ __launch_bounds__(kThreads) void dispatch_copy_kernel(const vec16* __restrict__ x,
+                                                                 const int32_t* __restrict__ slot,
+                                                                 int64_t total_chunks, int k_arg, int cpr, int shift,
+                                                                 vec16* __restrict__ send) {
+    constexpr int KM = KK > 0 ? KK : TAMOE_MAX_K;
+    const int k = KK > 0 ? KK : k_arg;
+    const int64_t base = (int64_t)blockIdx.x * (kThreads * U) + threadIdx.x;
+    vec16 v[U];
+    int32_t sl[U][KM];
+    int col[U];
+    bool live[U];
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int c = base + u * kThreads + threadIdx.x;
-            live[u] = false;
-            row[u] = 0;
-            col[u] = 0;
-            if (c < total) {
-                row[u] = c / cpr;
-                col[u] = c - row[u] * cpr;
-                for (int j = 0; j < k; ++j) live[u] |= s_slot[row[u] * k + j] >= 0;
-            }
-            if (live[u]) v[u] = __builtin_nontemporal_load(src + c);
-        }
+    for (int u = 0; u < U; ++u) {
+        const int64_t c = base + (int64_t)u * kThreads;
+        live[u] = false;
+        col[u] = 0;
+        if (c < total_chunks) {
+            int t;
+            split_chunk(c, total_chunks, cpr, shift, t, col[u]);
+            if (ROWU) t = __builtin_amdgcn_readfirstlane(t);
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            if (!live[u]) continue;
-            for (int j = 0; j < k; ++j) {
-                const int32_t s = s_slot[row[u] * k + j];
-                if (s >= 0) __builtin_nontemporal_store(v[u], send + (size_t)s * cpr + col[u]);
+            for (int j = 0; j < KM; ++j) {
+                sl[u][j] = j < k ? slot[(int64_t)t * k + j] : -1;
+                live[u] |= sl[u][j] >= 0;
             }
+            if (live[u]) v[u] = __builtin_nontemporal_load(x + c);
         }
     }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        if (!live[u]) continue;
+#pragma unroll
+        for (int j = 0; j < KM; ++j)
+            if (sl[u][j] >= 0) __builtin_nontemporal_store(v[u], send + (size_t)sl[u][j] * cpr + col[u]);
+    }
+}
+
+template <int KK, int U>
+static void launch_copy(const void* x, const int32_t* slot, int64_t S, int k, int cpr, void* send, hipStream_t st) {
+    const int64_t total = S * (int64_t)cpr;
+    const dim3 grid((unsigned)ceil_div(total, kThreads * U)), block(kThreads);
+    const vec16* src = static_cast<const vec16*>(x);
+    vec16* dst = static_cast<vec16*>(send);
+    const int shift = pow2_shift(cpr);
+    if (cpr % 64 == 0)
+        dispatch_copy_kernel<KK, U, true><<<grid, block, 0, st>>>(src, slot, total, k, cpr, shift, dst);
+    else
+        dispatch_copy_kernel<KK, U, false><<<grid, block, 0, st>>>(src, slot, total, k, cpr, shift, dst);
 }
 
 }  // namespace tamoe
@@ -194,9 +218,7 @@ extern "C" int tamoe_dispatch(const void* x, const int32_t* topk_idx, const int3
     const int64_t n_ct = count_tiles(S);
     if ((int64_t)k * n_ct > (int64_t)1 << 30)
         return fail(TAMOE_UNSUPPORTED, "%s: too many count tiles (%lld)", fn, (long long)n_ct);
-    const int row_bytes = d * elem_bytes(dtype);
-    const int cpr = row_bytes / 16;
-    if (cpr > 65536) return fail(TAMOE_UNSUPPORTED, "%s: rows longer than 1 MiB are not supported", fn);
+    const int cpr = d * elem_bytes(dtype) / 16;  // 16-byte chunks per row
 
     hipStream_t st = static_cast<hipStream_t>(stream);
     int32_t* tile_count = reinterpret_cast<int32_t*>(static_cast<char*>(ws) + lay.tile_count);
@@ -214,14 +236,24 @@ extern "C" int tamoe_dispatch(const void* x, const int32_t* topk_idx, const int3
     }
     if ((rc = check_launch(fn, "dispatch_scan_kernel")) != TAMOE_OK) return rc;
     if (S > 0) {
-        const int rt = row_tile(S, row_bytes);
-        const int64_t blocks = ceil_div(S, rt);
-        if (blocks > 0x7fffffff) return fail(TAMOE_UNSUPPORTED, "%s: too many row tiles", fn);
-        TraceScope tr("dispatch_scatter_kernel", st);
-        dispatch_scatter_kernel<4><<<dim3((unsigned)blocks), dim3(kThreads), 0, st>>>(
-            static_cast<const vec16*>(x), topk_idx, cap, tile_count, expert_offset, S, N, k, (int)n_ct, rt, cpr,
-            static_cast<vec16*>(send), slot);
-        if ((rc = check_launch(fn, "dispatch_scatter_kernel")) != TAMOE_OK) return rc;
+        if (ceil_div(S * (int64_t)cpr, kThreads * 1) > 0x7fffffff)
+            return fail(TAMOE_UNSUPPORTED, "%s: x is too large for one launch", fn);
+        {
+            TraceScope tr("dispatch_slot_kernel", st);
+            dispatch_slot_kernel<<<dim3((unsigned)ceil_div(S, kSlotTile)), dim3(kThreads), 0, st>>>(
+                topk_idx, cap, tile_count, expert_offset, S, N, k, (int)n_ct, slot);
+        }
+        if ((rc = check_launch(fn, "dispatch_slot_kernel")) != TAMOE_OK) return rc;
+        {
+            TraceScope tr("dispatch_copy_kernel", st);
+            if (k == 1)
+                launch_copy<1, 2>(x, slot, S, k, cpr, send, st);
+            else if (k == 2)
+                launch_copy<2, 1>(x, slot, S, k, cpr, send, st);
+            else
+                launch_copy<0, 1>(x, slot, S, k, cpr, send, st);
+        }
+        if ((rc = check_launch(fn, "dispatch_copy_kernel")) != TAMOE_OK) return rc;
     }
     return TAMOE_OK;
 }

@@ -152,7 +152,7 @@ __device__ __forceinline__ void store_block_partials(const float (*m_w)[NB * 32]
 
 // KTAIL: d is not a multiple of the 64-element K chunk (the last chunk is partly out of range).
 template <int NB, int WAVES, bool KTAIL>
-__global__ __launch_bounds__(WAVES * 64) void gate_bf16_kernel(
+__global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(2))) void gate_bf16_kernel(
     const uint16_t* __restrict__ x, const uint16_t* __restrict__ w, int64_t S, int d, int N, int k,
     float* __restrict__ logits, int32_t* __restrict__ topk_idx, float* __restrict__ topk_w,
     float* __restrict__ m_part, int32_t* __restrict__ c_part, int n_blocks) {
@@ -181,6 +181,11 @@ __global__ __launch_bounds__(WAVES * 64) void gate_bf16_kernel(
 
     const int n_chunks = (d + kKC - 1) / kKC;
     const vec16 zero = {0u, 0u, 0u, 0u};
+    // Rows of x are a power-of-two pitch apart, so the same K chunk of every row falls into the
+    // same few memory channels.  Workgroups would all walk K in step and queue on those channels;
+    // instead workgroup b starts its walk at chunk (17 b) mod n_chunks and wraps around.  (A dot
+    // product may be summed in any order; a token's scores depend on the order only in rounding.)
+    const int rot = (int)(((int64_t)blockIdx.x * 17) % n_chunks);
 
     // Both tiles go global -> registers -> LDS -> MFMA operands.  Unit u of a thread is the
     // 16-byte piece (unit & 7) of tile row (unit >> 3), unit = tid + u * T: eight consecutive
@@ -214,8 +219,12 @@ __global__ __launch_bounds__(WAVES * 64) void gate_bf16_kernel(
     }
     const int piece = tid & 7;  // (unit & 7) is the same for every unit of a thread: T % 8 == 0
 
+    auto chunk_at = [&](int step) {  // K chunk visited at pipeline step `step` (clamped past the end)
+        int c = (step < n_chunks ? step : n_chunks - 1) + rot;
+        return c >= n_chunks ? c - n_chunks : c;
+    };
     auto load_w = [&](int kc, vec16 (&dst)[WU]) {
-        kc = kc < n_chunks ? kc : n_chunks - 1;
+        kc = chunk_at(kc);
         int k0 = kc * kKC;
         bool in = true;
         if constexpr (KTAIL) {
@@ -229,7 +238,7 @@ __global__ __launch_bounds__(WAVES * 64) void gate_bf16_kernel(
         }
     };
     auto load_x = [&](int kc, vec16 (&dst)[XU]) {
-        kc = kc < n_chunks ? kc : n_chunks - 1;
+        kc = chunk_at(kc);
         int k0 = kc * kKC;
         if constexpr (KTAIL) k0 = (k0 + piece * 8 < d) ? k0 : d - 8 - piece * 8;
 #pragma unroll
@@ -268,27 +277,30 @@ __global__ __launch_bounds__(WAVES * 64) void gate_bf16_kernel(
         }
     };
 
-    // Software pipeline.  Chunk c of x is requested four iterations before it is used (four
-    // register sets), chunk c of W two iterations before (two sets); both are copied to the LDS
-    // double buffer one iteration before use.  A wavefront keeps up to 16 KiB of x in flight.
-    vec16 wr[2][WU];
+    // Software pipeline.  Chunk c of both tiles is requested four iterations before it is used
+    // (four register sets each; two for W when a thread owns more than four pieces of it) and is
+    // copied to the LDS double buffer one iteration before use.  Loads complete in order, so at
+    // the point where an iteration waits for chunk c+1 the chunks c+2 .. c+4 are still in flight:
+    // about 12 KiB of x per wavefront, which is what covers the HBM latency.
+    constexpr int DW = WU <= 4 ? 4 : 2;
+    vec16 wr[DW][WU];
     vec16 xr[4][XU];
     auto stage = [&](int kc, auto U) {   // u = kc mod 4, a compile-time constant at each call
         constexpr int u = decltype(U)::value;
-        load_w(kc + 2, wr[u & 1]);
+        load_w(kc + DW, wr[u % DW]);
         load_x(kc + 4, xr[u]);
+        __builtin_amdgcn_sched_barrier(0);  // keep the requests ahead of the MFMAs
         compute(u & 1);
-        store_w(wr[(u + 1) & 1], (u + 1) & 1);
+        store_w(wr[(u + 1) % DW], (u + 1) & 1);
         store_x(xr[(u + 1) & 3], (u + 1) & 1);
         __syncthreads();
     };
 
-    load_w(0, wr[0]);
-    load_x(0, xr[0]);
-    load_w(1, wr[1]);
-    load_x(1, xr[1]);
-    load_x(2, xr[2]);
-    load_x(3, xr[3]);
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+        if (c < DW) load_w(c, wr[c]);
+        load_x(c, xr[c]);
+    }
     store_w(wr[0], 0);
     store_x(xr[0], 0);
     __syncthreads();

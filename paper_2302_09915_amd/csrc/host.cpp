@@ -28,15 +28,6 @@ int gate_waves(int64_t S) {
     return 1;
 }
 
-int row_tile(int64_t S, int row_bytes) {
-    // Rows per scatter/combine workgroup: small enough for >= ~4 workgroups per compute unit,
-    // large enough that a workgroup moves at least 16 KiB.
-    int tile = 64;
-    while (tile > 4 && ceil_div(S, tile) < 1024) tile >>= 1;
-    while (tile < 64 && (int64_t)tile * row_bytes < 16384) tile <<= 1;
-    return tile;
-}
-
 Workspace workspace_layout(int64_t S, int N, int k) {
     Workspace w{};
     size_t off = 0;

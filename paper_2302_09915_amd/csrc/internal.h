@@ -33,10 +33,8 @@ inline int64_t gate_blocks(int64_t S) { return S == 0 ? 0 : ceil_div(S, 32 * (in
 // Upper bound of gate_blocks over every choice of waves.
 inline int64_t gate_blocks_max(int64_t S) { return ceil_div(S, 32); }
 
-// Dispatch: pairs are counted per "count tile" of kCountTile tokens; a scatter workgroup moves
-// the rows of a "row tile" of row_tile(S) tokens (a divisor of kCountTile).
+// Dispatch: pairs are counted per "count tile" of kCountTile tokens.
 constexpr int kCountTile = 1024;
-int row_tile(int64_t S, int row_bytes);
 inline int64_t count_tiles(int64_t S) { return ceil_div(S, kCountTile); }
 
 // ---- workspace layout -----------------------------------------------------------------------
@@ -48,6 +46,30 @@ struct Workspace {
     size_t total;
 };
 Workspace workspace_layout(int64_t S, int N, int k);
+
+// log2(v) if v is a power of two, else -1.
+inline int pow2_shift(int v) {
+    if (v <= 0 || (v & (v - 1)) != 0) return -1;
+    int s = 0;
+    while ((1 << s) < v) ++s;
+    return s;
+}
+
+// Chunk index -> (row, column) for a matrix of `cpr` 16-byte chunks per row.
+__device__ __forceinline__ void split_chunk(int64_t c, int64_t total, int cpr, int shift, int& row, int& col) {
+    if (shift >= 0) {
+        row = (int)(c >> shift);
+        col = (int)c & (cpr - 1);
+    } else if (total <= 0xffffffffll) {
+        const uint32_t r = (uint32_t)c / (uint32_t)cpr;
+        row = (int)r;
+        col = (int)((uint32_t)c - r * (uint32_t)cpr);
+    } else {
+        const int64_t r = c / cpr;
+        row = (int)r;
+        col = (int)(c - r * cpr);
+    }
+}
 
 // Common argument checks.  Return TAMOE_OK or a failure already recorded with fail().
 int check_shape(const char* fn, int64_t S, int N, int P, int k);
