@@ -33,6 +33,45 @@ __device__ __forceinline__ int expert_of(int nb, int v, int half) {
     return nb * 32 + ((v >> 2) << 3) + (half << 2) + (v & 3);
 }
 
+// value of lane (lane ^ MASK) within each half of the wavefront (MASK < 32), through the
+// LDS crossbar without touching LDS memory
+template <int MASK>
+__device__ __forceinline__ float swizzle_xor(float v) {
+    return __int_as_float(__builtin_amdgcn_ds_swizzle(__float_as_int(v), (MASK << 10) | 0x1f));
+}
+
+// One level of a transposed butterfly over the 32 token lanes: lanes that differ in bit S
+// exchange half of their SIZE values and add, so that each keeps SIZE/2 partial sums (those
+// whose index has bit 0 equal to the lane's bit S).  After log2 levels a lane holds the complete
+// sums of SIZE/32 indices instead of every lane holding all of them: SIZE-1 exchanges instead of
+// 5*SIZE.  The summation tree is fixed, so the result is the same on every run.
+template <int SIZE, int S>
+__device__ __forceinline__ void transpose_reduce(float (&a)[SIZE], int lane) {
+    if constexpr (S < 5) {
+        if constexpr (SIZE >= 2) {
+            const bool up = (lane >> S) & 1;
+            float nxt[SIZE / 2];
+#pragma unroll
+            for (int i = 0; i < SIZE / 2; ++i) {
+                const float keep = up ? a[2 * i + 1] : a[2 * i];
+                const float send = up ? a[2 * i] : a[2 * i + 1];
+                nxt[i] = keep + swizzle_xor<(1 << S)>(send);
+            }
+            transpose_reduce<SIZE / 2, S + 1>(nxt, lane);
+#pragma unroll
+            for (int i = 0; i < SIZE / 2; ++i) a[i] = nxt[i];
+        } else {
+            a[0] += swizzle_xor<(1 << S)>(a[0]);
+            transpose_reduce<SIZE, S + 1>(a, lane);
+        }
+    }
+}
+
+// (value, index) order of the selection: higher score first, equal scores to the lower index
+__device__ __forceinline__ bool ranks_before(float av, int ai, float bv, int bi) {
+    return av > bv || (av == bv && ai < bi);
+}
+
 // Selection on a 32-token tile held in the accumulator layout described above.
 // sc[nb][v]: score of expert_of(nb, v, lane>>5) for token `token` (lane & 31 within the tile).
 // m_wave: LDS, [>= NB*32] floats owned by this wavefront; hist: LDS, [>= NB*32] ints of the block.
@@ -50,58 +89,97 @@ __device__ __forceinline__ void select_tile(float (&sc)[NB][16], int lane, int64
                 if (e < N) logits[token * N + e] = sc[nb][v];
             }
     }
+    if (N < NB * 32) {  // uniform
 #pragma unroll
-    for (int nb = 0; nb < NB; ++nb)
+        for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
-        for (int v = 0; v < 16; ++v)
-            if (expert_of(nb, v, half) >= N) sc[nb][v] = -INFINITY;
+            for (int v = 0; v < 16; ++v)
+                if (expert_of(nb, v, half) >= N) sc[nb][v] = -INFINITY;
+    }
 
-    // top-k: k passes; each pass takes the best score that comes after the previous pick in the
-    // order (score descending, expert index ascending).
     float sel_v[TAMOE_MAX_K];
     int sel_i[TAMOE_MAX_K];
-    float last_v = INFINITY;
-    int last_i = -1;
 #pragma unroll
     for (int j = 0; j < TAMOE_MAX_K; ++j) {
         sel_v[j] = -INFINITY;
         sel_i[j] = -1;
-        if (j < k) {
-            float bv = -INFINITY;
-            int bi = INT_MAX;
+    }
+    if (k <= 2) {
+        // one pass keeps the best two of the lane (values are visited in ascending expert index,
+        // so a strict '>' leaves equal scores with the lower index), then the two halves merge
+        float b1v = -INFINITY, b2v = -INFINITY;
+        int b1i = INT_MAX, b2i = INT_MAX;
 #pragma unroll
-            for (int nb = 0; nb < NB; ++nb)
+        for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
-                for (int v = 0; v < 16; ++v) {  // ascending expert index inside a lane
-                    const float a = sc[nb][v];
-                    const int e = expert_of(nb, v, half);
-                    const bool after = (a < last_v) || (a == last_v && e > last_i);
-                    if (after && a > bv) {
-                        bv = a;
-                        bi = e;
-                    }
-                }
-            const float ov = __shfl_xor(bv, 32);
-            const int oi = __shfl_xor(bi, 32);
-            if (ov > bv || (ov == bv && oi < bi)) {
-                bv = ov;
-                bi = oi;
+            for (int v = 0; v < 16; ++v) {
+                const float a = sc[nb][v];
+                const int e = expert_of(nb, v, half);
+                const bool g1 = a > b1v, g2 = a > b2v;
+                b2v = g1 ? b1v : (g2 ? a : b2v);
+                b2i = g1 ? b1i : (g2 ? e : b2i);
+                b1v = g1 ? a : b1v;
+                b1i = g1 ? e : b1i;
             }
-            last_v = bv;
-            last_i = bi;
-            sel_v[j] = bv;
-            sel_i[j] = bi == INT_MAX ? -1 : bi;
+        const float o1v = __shfl_xor(b1v, 32), o2v = __shfl_xor(b2v, 32);
+        const int o1i = __shfl_xor(b1i, 32), o2i = __shfl_xor(b2i, 32);
+        const bool mine = ranks_before(b1v, b1i, o1v, o1i);
+        sel_v[0] = mine ? b1v : o1v;
+        sel_i[0] = mine ? b1i : o1i;
+        // runner-up: the loser of the two leaders against the winner's own second
+        const float cv = mine ? o1v : b1v, dv = mine ? b2v : o2v;
+        const int ci = mine ? o1i : b1i, di = mine ? b2i : o2i;
+        const bool c_first = ranks_before(cv, ci, dv, di);
+        sel_v[1] = c_first ? cv : dv;
+        sel_i[1] = c_first ? ci : di;
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+            if (sel_i[j] == INT_MAX) sel_i[j] = -1;
+    } else {
+        // k passes; each takes the best score that comes after the previous pick in the order
+        // (score descending, expert index ascending)
+        float last_v = INFINITY;
+        int last_i = -1;
+#pragma unroll
+        for (int j = 0; j < TAMOE_MAX_K; ++j) {
+            if (j < k) {
+                float bv = -INFINITY;
+                int bi = INT_MAX;
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+                    for (int v = 0; v < 16; ++v) {
+                        const float a = sc[nb][v];
+                        const int e = expert_of(nb, v, half);
+                        const bool after = (a < last_v) || (a == last_v && e > last_i);
+                        if (after && a > bv) {
+                            bv = a;
+                            bi = e;
+                        }
+                    }
+                const float ov = __shfl_xor(bv, 32);
+                const int oi = __shfl_xor(bi, 32);
+                if (ranks_before(ov, oi, bv, bi)) {
+                    bv = ov;
+                    bi = oi;
+                }
+                last_v = bv;
+                last_i = bi;
+                sel_v[j] = bv;
+                sel_i[j] = bi == INT_MAX ? -1 : bi;
+            }
         }
     }
 
-    // softmax: the first pick is the row maximum
+    // softmax: the first pick is the row maximum.  exp(t) = 2^(t * log2 e) on the hardware
+    // exponential; for t in [-100, 0] the product's rounding keeps the relative error below 1e-5.
     const float mx = sel_v[0];
     float part = 0.f;
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
-            sc[nb][v] = expf(sc[nb][v] - mx);
+            sc[nb][v] = __builtin_amdgcn_exp2f((sc[nb][v] - mx) * 1.44269504088896340736f);
             part += sc[nb][v];
         }
     const float den = part + __shfl_xor(part, 32);
@@ -112,26 +190,34 @@ __device__ __forceinline__ void select_tile(float (&sc)[NB][16], int lane, int64
         for (int j = 0; j < TAMOE_MAX_K; ++j) {
             if (j < k) {
                 topk_idx[token * k + j] = sel_i[j];
-                topk_w[token * k + j] = expf(sel_v[j] - mx) / den;
+                topk_w[token * k + j] = __builtin_amdgcn_exp2f((sel_v[j] - mx) * 1.44269504088896340736f) / den;
                 if (sel_i[j] >= 0 && sel_i[j] < N) atomicAdd(&hist[sel_i[j]], 1);
             }
         }
     }
 
     // per-expert probability sums over the 32 tokens of the tile
+    constexpr int V = NB * 16;
+    float p[V];
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            float p = token_ok ? sc[nb][v] * inv : 0.f;
-            p += __shfl_xor(p, 1);
-            p += __shfl_xor(p, 2);
-            p += __shfl_xor(p, 4);
-            p += __shfl_xor(p, 8);
-            p += __shfl_xor(p, 16);
-            const int e = expert_of(nb, v, half);
-            if ((lane & 31) == 0 && e < N) m_wave[e] = p;
+        for (int v = 0; v < 16; ++v) p[nb * 16 + v] = token_ok ? sc[nb][v] * inv : 0.f;
+    transpose_reduce<V, 0>(p, lane);
+    // lane r now holds the sums of the value indices q = r + 32*i (i < V/32), or, when V < 32, of
+    // q = r mod V (in every lane that shares it)
+    const int r = lane & 31;
+    if constexpr (V >= 32) {
+#pragma unroll
+        for (int i = 0; i < V / 32; ++i) {
+            const int q = r + 32 * i;
+            const int e = expert_of(q >> 4, q & 15, half);
+            if (e < N) m_wave[e] = p[i];
         }
+    } else {
+        const int e = expert_of(0, r & 15, half);
+        if (r < 16 && e < N) m_wave[e] = p[0];
+    }
 }
 
 // Folds the wavefronts' sums and the block histogram into the per-workgroup partial arrays
@@ -152,7 +238,8 @@ __device__ __forceinline__ void store_block_partials(const float (*m_w)[NB * 32]
 
 // KTAIL: d is not a multiple of the 64-element K chunk (the last chunk is partly out of range).
 template <int NB, int WAVES, bool KTAIL>
-__global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu(2))) void gate_bf16_kernel(
+__global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu((NB == 4 && WAVES < 4) ? 1 : 2)))
+void gate_bf16_kernel(
     const uint16_t* __restrict__ x, const uint16_t* __restrict__ w, int64_t S, int d, int N, int k,
     float* __restrict__ logits, int32_t* __restrict__ topk_idx, float* __restrict__ topk_w,
     float* __restrict__ m_part, int32_t* __restrict__ c_part, int n_blocks) {
