@@ -176,9 +176,13 @@ int tamoe_combine(const void* recv, int64_t K_rows, const int32_t* slot, const f
  * tamoe_trace_stop waits for the recorded events and returns the number of records (>= 0), or
  * a negative tamoe_status.  tamoe_trace_get copies record i: the kernel's name (truncated to
  * name_len-1 characters) and its duration in milliseconds.  tamoe_trace_clear destroys the
- * events.  One trace at a time, process-wide; not thread-safe.  All pointers host.
+ * events.  tamoe_trace_filter restricts the bracketing to launches of the kernel with the given
+ * name (NULL: every kernel again), so that a benchmark can time one kernel with two event records
+ * per step instead of two per launch; it may be called at any time.
+ * One trace at a time, process-wide; not thread-safe.  All pointers host.
  */
 int tamoe_trace_start(int max_launches);
+int tamoe_trace_filter(const char* kernel_name);
 int tamoe_trace_stop(void);
 int tamoe_trace_get(int i, char* name, size_t name_len, float* ms);
 int tamoe_trace_clear(void);

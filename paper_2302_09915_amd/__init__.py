@@ -32,7 +32,7 @@ OK, INVALID_ARG, UNSUPPORTED, WORKSPACE_TOO_SMALL, HIP_ERROR = 0, 1, 2, 3, 4
 EXPORTS = (
     "tamoe_version", "tamoe_last_error", "tamoe_topo_pattern", "tamoe_workspace_bytes",
     "tamoe_gate", "tamoe_select", "tamoe_aux_loss", "tamoe_dispatch", "tamoe_combine",
-    "tamoe_trace_start", "tamoe_trace_stop", "tamoe_trace_get", "tamoe_trace_clear", "tamoe_copy_probe",
+    "tamoe_trace_start", "tamoe_trace_filter", "tamoe_trace_stop", "tamoe_trace_get", "tamoe_trace_clear", "tamoe_copy_probe",
 )
 
 
@@ -75,6 +75,8 @@ def lib() -> ctypes.CDLL:
     L.tamoe_combine.argtypes = [vp, i64, vp, vp, i32, i64, i32, i32, vp, vp]
     L.tamoe_trace_start.restype = i32
     L.tamoe_trace_start.argtypes = [i32]
+    L.tamoe_trace_filter.restype = i32
+    L.tamoe_trace_filter.argtypes = [ctypes.c_char_p]
     L.tamoe_trace_stop.restype = i32
     L.tamoe_trace_stop.argtypes = []
     L.tamoe_trace_get.restype = i32
@@ -217,6 +219,10 @@ def tamoe_combine(recv, K_rows: int, slot, topk_w, y, stream=None) -> None:
 
 def tamoe_trace_start(max_launches: int) -> None:
     _check(lib().tamoe_trace_start(max_launches))
+
+
+def tamoe_trace_filter(kernel_name: Optional[str]) -> None:
+    _check(lib().tamoe_trace_filter(None if kernel_name is None else kernel_name.encode()))
 
 
 def tamoe_trace_stop() -> int:

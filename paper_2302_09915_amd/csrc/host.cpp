@@ -91,9 +91,11 @@ struct TraceRecord {
 std::vector<TraceRecord> g_records;   // capacity fixed by tamoe_trace_start
 size_t g_used = 0;
 bool g_open = false;                  // a begin without its end
+char g_filter[64] = "";               // "" = every kernel
 }  // namespace
 
 void trace_begin(const char* kernel, hipStream_t st) {
+    if (g_filter[0] != '\0' && std::strcmp(kernel, g_filter) != 0) return;
     if (g_used >= g_records.size()) {
         g_trace_on = false;
         return;
@@ -140,6 +142,18 @@ extern "C" int tamoe_trace_start(int max_launches) {
         g_records.push_back(r);
     }
     g_trace_on = true;
+    return TAMOE_OK;
+}
+
+extern "C" int tamoe_trace_filter(const char* kernel_name) {
+    clear_error();
+    if (kernel_name == nullptr) {
+        g_filter[0] = '\0';
+        return TAMOE_OK;
+    }
+    if (std::strlen(kernel_name) >= sizeof(g_filter))
+        return fail(TAMOE_INVALID_ARG, "tamoe_trace_filter: kernel name longer than %zu characters", sizeof(g_filter) - 1);
+    std::strcpy(g_filter, kernel_name);
     return TAMOE_OK;
 }
 

@@ -377,3 +377,95 @@ def test_aux_loss_closed_forms_on_device(T):
     la = T.aux_loss(m, c, None, P, S).item()
     assert lt == pytest.approx(k / (N // P), rel=1e-5)
     assert la == pytest.approx(k / N, rel=1e-5)
+
+
+# ---------------------------------------------------------------------------
+# bench aids: kernel trace and copy probe
+# ---------------------------------------------------------------------------
+def test_trace_and_copy_probe(T):
+    src = torch.arange(1 << 20, dtype=torch.int32, device="cuda")
+    dst = torch.zeros_like(src)
+    T.tamoe_trace_start(8)
+    for _ in range(3):
+        T.tamoe_copy_probe(src, dst)
+    n = T.tamoe_trace_stop()
+    assert n == 3
+    for i in range(n):
+        name, ms = T.tamoe_trace_get(i)
+        assert name == "copy_probe_kernel" and 0.0 < ms < 50.0
+    assert torch.equal(src, dst)
+    # a filter on another kernel's name records nothing; clearing it records again
+    T.tamoe_trace_filter("combine_kernel")
+    T.tamoe_trace_start(8)
+    T.tamoe_copy_probe(src, dst)
+    assert T.tamoe_trace_stop() == 0
+    T.tamoe_trace_filter(None)
+    T.tamoe_trace_start(1)
+    T.tamoe_copy_probe(src, dst)
+    T.tamoe_copy_probe(src, dst)            # beyond the capacity: not recorded, still executed
+    assert T.tamoe_trace_stop() == 1
+    T.tamoe_trace_clear()
+    with pytest.raises(T.TamoeError):
+        T.tamoe_trace_get(0)
+
+
+def test_step_can_be_captured_in_a_graph(T, oracle):
+    """The library only enqueues kernels on the given stream (no allocation, no memset), so a whole
+    step replays from a HIP graph; every replay must reproduce the eager result."""
+    wl = W.WORKLOADS["small"]
+    inp = W.make_inputs(wl)
+    beta, level = W.topology(wl)
+    _, pen, cap = T.tamoe_topo_pattern(beta, level, wl.P, wl.N, 0, wl.k, wl.S, wl.capacity_factor, 0)
+    x, w = to_dev(inp["x"], wl.dtype), to_dev(inp["w"], wl.dtype)
+    S, d, N, P, k = wl.S, wl.d, wl.N, wl.P, wl.k
+    dev = x.device
+    ws = T.workspace(S, d, N, P, k, wl.dtype)
+    bufs = {
+        "topk_idx": torch.empty((S, k), dtype=torch.int32, device=dev),
+        "topk_w": torch.empty((S, k), dtype=torch.float32, device=dev),
+        "m": torch.empty((N,), dtype=torch.float32, device=dev),
+        "c_expert": torch.empty((N,), dtype=torch.int32, device=dev),
+        "c_device": torch.empty((P,), dtype=torch.int32, device=dev),
+        "loss": torch.empty((1,), dtype=torch.float32, device=dev),
+        "send": torch.empty((S * k, d), dtype=x.dtype, device=dev),
+        "slot": torch.empty((S, k), dtype=torch.int32, device=dev),
+        "kept": torch.empty((N,), dtype=torch.int32, device=dev),
+        "off": torch.empty((N + 1,), dtype=torch.int32, device=dev),
+        "scd": torch.empty((P,), dtype=torch.int32, device=dev),
+        "y": torch.empty((S, d), dtype=x.dtype, device=dev),
+    }
+    pen_d, cap_d = torch.from_numpy(pen).cuda(), torch.from_numpy(cap).cuda()
+
+    def step(xin):
+        b = bufs
+        T.tamoe_gate(xin, w, P, k, None, b["topk_idx"], b["topk_w"], b["m"], b["c_expert"], b["c_device"], ws)
+        T.tamoe_aux_loss(b["m"], b["c_expert"], pen_d, P, S, b["loss"])
+        T.tamoe_dispatch(xin, b["topk_idx"], cap_d, N, P, b["send"], b["slot"], b["kept"], b["off"], b["scd"], ws)
+        T.tamoe_combine(b["send"], S * k, b["slot"], b["topk_w"], b["y"])
+
+    x_in = x.clone()
+    step(x_in)
+    torch.cuda.synchronize()
+    eager = {n: t.clone() for n, t in bufs.items()}
+    K = int(eager["off"][-1].item())
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        step(x_in)
+    for rep in range(3):
+        for t in bufs.values():
+            t.zero_()                      # eager work between the replays
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        for n in bufs:
+            a, b = eager[n], bufs[n]
+            if n == "send":
+                a, b = a[:K], b[:K]
+            assert torch.equal(a.view(torch.uint8), b.view(torch.uint8)), (n, rep)
+    # new input through the same graph: permuting the tokens permutes the routing
+    perm = torch.randperm(S, device=dev)
+    x_in.copy_(x[perm])
+    g.replay()
+    torch.cuda.synchronize()
+    assert torch.equal(bufs["topk_idx"], eager["topk_idx"][perm])
+    assert torch.equal(bufs["c_expert"], eager["c_expert"])
