@@ -540,7 +540,11 @@ static void launch_gate_bf16(int waves, int64_t blocks, hipStream_t st, const ui
 #define TAMOE_GATE_LAUNCH(WV, KT)                                                                                 \
     gate_bf16_kernel<NB, WV, KT><<<grid, dim3(WV * 64), 0, st>>>(x, w, S, d, N, k, logits, topk_idx, topk_w, m_part, \
                                                                   c_part, (int)blocks)
-    if (waves == 4) {
+    if (waves == 8) {
+        if constexpr (NB >= 2) {
+            if (ktail) TAMOE_GATE_LAUNCH(8, true); else TAMOE_GATE_LAUNCH(8, false);
+        }
+    } else if (waves == 4) {
         if (ktail) TAMOE_GATE_LAUNCH(4, true); else TAMOE_GATE_LAUNCH(4, false);
     } else if (waves == 2) {
         if (ktail) TAMOE_GATE_LAUNCH(2, true); else TAMOE_GATE_LAUNCH(2, false);
@@ -629,8 +633,8 @@ extern "C" int tamoe_gate(const void* x, const void* w, int dtype, int64_t S, in
     int32_t* c_part = reinterpret_cast<int32_t*>(static_cast<char*>(ws) + lay.c_part);
     int64_t blocks = 0;
     if (S > 0 && dtype == TAMOE_BF16) {
-        const int waves = gate_waves(S);
-        blocks = gate_blocks(S);
+        const int waves = gate_waves(S, N);
+        blocks = ceil_div(S, 32 * (int64_t)waves);
         if (blocks > 0x7fffffff) return fail(TAMOE_UNSUPPORTED, "%s: too many token tiles", fn);
         const uint16_t* xb = static_cast<const uint16_t*>(x);
         const uint16_t* wb = static_cast<const uint16_t*>(w);

@@ -21,8 +21,10 @@ int fail(int code, const char* fmt, ...) {
 
 void clear_error() { g_err[0] = '\0'; }
 
-int gate_waves(int64_t S) {
-    // aim for at least two workgroups per compute unit (256 CUs)
+int gate_waves(int64_t S, int N) {
+    // eight wavefronts (one workgroup per compute unit, 256 CUs) halve the traffic of W once
+    // there are enough tokens; otherwise aim for at least two workgroups per compute unit
+    if (N > 32 && ceil_div(S, 256) >= 256) return 8;
     if (ceil_div(S, 128) >= 512) return 4;
     if (ceil_div(S, 64) >= 512) return 2;
     return 1;

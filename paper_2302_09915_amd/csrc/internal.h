@@ -28,9 +28,8 @@ inline int elem_bytes(int dtype) { return dtype == TAMOE_F32 ? 4 : 2; }
 // Gate: a workgroup of 64*waves threads scores 32*waves tokens (one 32-token MFMA column block
 // per wavefront).  More wavefronts per workgroup share one LDS copy of the W tile; fewer give
 // more workgroups when S is small.
-int gate_waves(int64_t S);
-inline int64_t gate_blocks(int64_t S) { return S == 0 ? 0 : ceil_div(S, 32 * (int64_t)gate_waves(S)); }
-// Upper bound of gate_blocks over every choice of waves.
+int gate_waves(int64_t S, int N);
+// Upper bound of the number of gate workgroups over every choice of waves.
 inline int64_t gate_blocks_max(int64_t S) { return ceil_div(S, 32); }
 
 // Dispatch: pairs are counted per "count tile" of kCountTile tokens.
