@@ -165,6 +165,29 @@ def main():
     copy_us = float(np.median([T.tamoe_trace_get(i)[1] for i in range(n_rec)])) * 1e3
     copy_gbs = 2.0 * S * d * b / (copy_us * 1e-6) / 1e9
 
+    # row-mix yardsticks on the realised slot table (k = 2, rows a multiple of 1 KiB): the scatter's
+    # and the combine's memory operations with nothing else around them
+    mix = None
+    if k == 2 and (d * b) % 1024 == 0:
+        r0 = slot[:, 0].contiguous()
+        r1 = slot[:, 1].contiguous()
+        T.tamoe_trace_start(16)
+        for _ in range(5):
+            T.tamoe_mix_probe(x, send, r0, r1, 1, None)
+        n_rec = T.tamoe_trace_stop()
+        sc_us = float(np.median([T.tamoe_trace_get(i)[1] for i in range(n_rec)])) * 1e3
+        T.tamoe_trace_start(16)
+        for _ in range(5):
+            T.tamoe_mix_probe(send, y, r0, r1, 2, None)
+        n_rec = T.tamoe_trace_stop()
+        ga_us = float(np.median([T.tamoe_trace_get(i)[1] for i in range(n_rec)])) * 1e3
+        K0 = int((slot >= 0).sum().item())
+        live0 = int((slot >= 0).any(dim=1).sum().item())
+        mix = {"scatter_1r2w": {"median_us": round(sc_us, 2),
+                                "GBs": round((live0 + K0) * d * b / (sc_us * 1e-6) / 1e9, 1)},
+               "gather_2r1w": {"median_us": round(ga_us, 2),
+                               "GBs": round((K0 + S) * d * b / (ga_us * 1e-6) / 1e9, 1)}}
+
     launches_per_step = 9
 
     def collect():
@@ -275,6 +298,7 @@ def main():
         "roofline": roofline,
         "copy_probe": {"bytes_moved": int(2 * S * d * b), "median_us": round(copy_us, 2),
                        "GBs": round(copy_gbs, 1), "frac_of_hbm_peak": round(copy_gbs / HBM_PEAK_GBS, 4)},
+        "mix_probe": mix,
         "kernels": kernels,
         "l_topo": float(loss.item()),
         "mode": "graph replay" if args.graph else "eager",

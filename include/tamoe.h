@@ -196,6 +196,19 @@ int tamoe_trace_clear(void);
  */
 int tamoe_copy_probe(const void* src, void* dst, size_t bytes, void* stream);
 
+/*
+ * Row-mix yardsticks for benchmarks (not steps of the path): the bare memory operations of the
+ * scatter and of the combine on caller-given row tables, with none of the method's logic.
+ *   mode 1: b[row0[t]][:] = b[row1[t]][:] = a[t][:]      for t < rows   (one read, two writes)
+ *   mode 2: b[t][:] = a[row0[t]][:] xor a[row1[t]][:]    for t < rows   (two reads, one write)
+ * Rows are row_bytes long (a positive multiple of 1024).  `other_rows` is the number of rows of
+ * the matrix that row0/row1 index (b in mode 1, a in mode 2); entries outside [0, other_rows)
+ * are skipped.  In mode 1 every row number may occur at most once over both tables.  a, b, row0
+ * [rows], row1 [rows]: device; a and b 16-byte aligned and not overlapping.
+ */
+int tamoe_mix_probe(const void* a, void* b, const int32_t* row0, const int32_t* row1, int64_t rows,
+                    int64_t other_rows, int row_bytes, int mode, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

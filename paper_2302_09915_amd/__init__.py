@@ -32,7 +32,7 @@ OK, INVALID_ARG, UNSUPPORTED, WORKSPACE_TOO_SMALL, HIP_ERROR = 0, 1, 2, 3, 4
 EXPORTS = (
     "tamoe_version", "tamoe_last_error", "tamoe_topo_pattern", "tamoe_workspace_bytes",
     "tamoe_gate", "tamoe_select", "tamoe_aux_loss", "tamoe_dispatch", "tamoe_combine",
-    "tamoe_trace_start", "tamoe_trace_filter", "tamoe_trace_stop", "tamoe_trace_get", "tamoe_trace_clear", "tamoe_copy_probe",
+    "tamoe_trace_start", "tamoe_trace_filter", "tamoe_trace_stop", "tamoe_trace_get", "tamoe_trace_clear", "tamoe_copy_probe", "tamoe_mix_probe",
 )
 
 
@@ -85,6 +85,8 @@ def lib() -> ctypes.CDLL:
     L.tamoe_trace_clear.argtypes = []
     L.tamoe_copy_probe.restype = i32
     L.tamoe_copy_probe.argtypes = [vp, vp, sz, vp]
+    L.tamoe_mix_probe.restype = i32
+    L.tamoe_mix_probe.argtypes = [vp, vp, vp, vp, i64, i64, i32, i32, vp]
     _lib = L
     return L
 
@@ -248,6 +250,23 @@ def tamoe_copy_probe(src, dst, stream=None) -> None:
     if dst.numel() * dst.element_size() < nbytes:
         raise TamoeError(INVALID_ARG, "dst is smaller than src")
     _check(lib().tamoe_copy_probe(_dev(src, None, "src"), _dev(dst, None, "dst"), nbytes, _stream(stream)))
+
+
+def tamoe_mix_probe(a, b, row0, row1, mode: int, stream=None) -> None:
+    """mode 1: b[row0[t]] = b[row1[t]] = a[t]; mode 2: b[t] = a[row0[t]] ^ a[row1[t]].  a, b: [rows, d] matrices."""
+    rows = row0.shape[0]
+    if mode == 1:
+        row_bytes, other = a.shape[1] * a.element_size(), b.shape[0]
+        if a.shape[0] < rows:
+            raise TamoeError(INVALID_ARG, "a has fewer rows than the row tables")
+    else:
+        row_bytes, other = b.shape[1] * b.element_size(), a.shape[0]
+        if b.shape[0] < rows:
+            raise TamoeError(INVALID_ARG, "b has fewer rows than the row tables")
+    if a.shape[1] * a.element_size() != b.shape[1] * b.element_size():
+        raise TamoeError(INVALID_ARG, "a and b must have rows of the same length")
+    _check(lib().tamoe_mix_probe(_dev(a, None, "a"), _dev(b, None, "b"), _dev(row0, torch.int32, "row0"),
+                                 _dev(row1, torch.int32, "row1"), rows, other, row_bytes, mode, _stream(stream)))
 
 
 # ---- allocating helpers -------------------------------------------------------------------

@@ -24,9 +24,68 @@ __global__ __launch_bounds__(kProbeThreads) void copy_probe_kernel(const vec16* 
     }
 }
 
+// Row-mix yardsticks: the memory operations of the scatter (one row read, two row writes) and of
+// the combine (two row reads, one row write) on given row tables, with nothing else around them.
+// One 16-byte chunk per thread; a row is a multiple of 1 KiB, so a wavefront stays inside one row
+// and reads its two row numbers through the scalar unit.  Negative or out-of-range rows are skipped.
+template <int MODE>
+__global__ __launch_bounds__(kProbeThreads) void mix_probe_kernel(const vec16* __restrict__ a, vec16* __restrict__ b,
+                                                                  const int32_t* __restrict__ row0,
+                                                                  const int32_t* __restrict__ row1, int64_t total,
+                                                                  int cpr, int64_t other_rows) {
+    const int64_t c = (int64_t)blockIdx.x * kProbeThreads + threadIdx.x;
+    if (c >= total) return;
+    const int t = __builtin_amdgcn_readfirstlane((int)(c / cpr));
+    const int col = (int)(c - (int64_t)t * cpr);
+    const int32_t r0 = row0[t], r1 = row1[t];
+    const bool ok0 = r0 >= 0 && r0 < other_rows, ok1 = r1 >= 0 && r1 < other_rows;
+    if (MODE == 1) {
+        if (!ok0 && !ok1) return;
+        const vec16 v = __builtin_nontemporal_load(a + c);
+        if (ok0) __builtin_nontemporal_store(v, b + (size_t)r0 * cpr + col);
+        if (ok1) __builtin_nontemporal_store(v, b + (size_t)r1 * cpr + col);
+    } else {
+        vec16 v = {0u, 0u, 0u, 0u};
+        if (ok0) v = __builtin_nontemporal_load(a + (size_t)r0 * cpr + col);
+        if (ok1) v ^= __builtin_nontemporal_load(a + (size_t)r1 * cpr + col);
+        __builtin_nontemporal_store(v, b + c);
+    }
+}
+
 }  // namespace tamoe
 
 using namespace tamoe;
+
+extern "C" int tamoe_mix_probe(const void* a, void* b, const int32_t* row0, const int32_t* row1, int64_t rows,
+                               int64_t other_rows, int row_bytes, int mode, void* stream) {
+    const char* fn = "tamoe_mix_probe";
+    clear_error();
+    int rc;
+    if (mode != 1 && mode != 2) return fail(TAMOE_INVALID_ARG, "%s: mode %d is neither 1 (scatter) nor 2 (gather)", fn, mode);
+    if (rows < 0 || other_rows < 0) return fail(TAMOE_INVALID_ARG, "%s: negative row count", fn);
+    if (row_bytes <= 0 || row_bytes % 1024 != 0)
+        return fail(TAMOE_UNSUPPORTED, "%s: row_bytes = %d is not a positive multiple of 1024", fn, row_bytes);
+    if (rows == 0) return TAMOE_OK;
+    if ((rc = check_ptr(fn, "a", a, 16)) != TAMOE_OK) return rc;
+    if ((rc = check_ptr(fn, "b", b, 16)) != TAMOE_OK) return rc;
+    if ((rc = check_ptr(fn, "row0", row0, 4)) != TAMOE_OK) return rc;
+    if ((rc = check_ptr(fn, "row1", row1, 4)) != TAMOE_OK) return rc;
+    const int cpr = row_bytes / 16;
+    const int64_t total = rows * cpr;
+    const int64_t blocks = ceil_div(total, kProbeThreads);
+    if (rows >= ((int64_t)1 << 31) || blocks > 0x7fffffff) return fail(TAMOE_UNSUPPORTED, "%s: too many rows", fn);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    {
+        TraceScope tr(mode == 1 ? "mix_probe_scatter_kernel" : "mix_probe_gather_kernel", st);
+        if (mode == 1)
+            mix_probe_kernel<1><<<dim3((unsigned)blocks), dim3(kProbeThreads), 0, st>>>(
+                static_cast<const vec16*>(a), static_cast<vec16*>(b), row0, row1, total, cpr, other_rows);
+        else
+            mix_probe_kernel<2><<<dim3((unsigned)blocks), dim3(kProbeThreads), 0, st>>>(
+                static_cast<const vec16*>(a), static_cast<vec16*>(b), row0, row1, total, cpr, other_rows);
+    }
+    return check_launch(fn, "mix_probe_kernel");
+}
 
 extern "C" int tamoe_copy_probe(const void* src, void* dst, size_t bytes, void* stream) {
     const char* fn = "tamoe_copy_probe";

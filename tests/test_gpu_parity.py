@@ -469,3 +469,25 @@ def test_step_can_be_captured_in_a_graph(T, oracle):
     torch.cuda.synchronize()
     assert torch.equal(bufs["topk_idx"], eager["topk_idx"][perm])
     assert torch.equal(bufs["c_expert"], eager["c_expert"])
+
+
+def test_mix_probe_moves_the_rows_it_is_told_to(T):
+    rows, d = 300, 512                                   # 1 KiB rows of bf16
+    a = torch.randn((rows, d), device="cuda").to(torch.bfloat16)
+    perm = torch.randperm(2 * rows, device="cuda").to(torch.int32)
+    r0, r1 = perm[:rows].contiguous(), perm[rows:].contiguous()
+    r1[7] = -1                                          # skipped
+    b = torch.zeros((2 * rows, d), dtype=torch.bfloat16, device="cuda")
+    T.tamoe_mix_probe(a, b, r0, r1, 1)
+    torch.cuda.synchronize()
+    ai, bi = a.view(torch.int16), b.view(torch.int16)
+    assert torch.equal(bi[r0.long()], ai)
+    keep = r1 >= 0
+    assert torch.equal(bi[r1[keep].long()], ai[keep])
+    out = torch.empty_like(a)
+    T.tamoe_mix_probe(b, out, r0, r1, 2)
+    torch.cuda.synchronize()
+    expect = torch.where(keep[:, None], torch.zeros_like(ai), ai)   # x ^ x = 0 where both rows exist
+    assert torch.equal(out.view(torch.int16), expect)
+    with pytest.raises(T.TamoeError):
+        T.tamoe_mix_probe(a[:, :100].contiguous(), b[:, :100].contiguous(), r0, r1, 1)
