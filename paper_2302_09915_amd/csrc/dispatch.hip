@@ -24,6 +24,27 @@ namespace tamoe {
 constexpr int kThreads = 256;
 constexpr int kSlotTile = 64;  // tokens per slot-assignment workgroup; divides kCountTile
 
+// hist[j*N + e] += number of pairs p in [p_begin, p_end) with idx[p] == e, j = p mod k (LDS integer
+// atomics).  Eight loads per thread are issued before the first is used: a loop that consumes each
+// index as it arrives pays one memory round trip per iteration.
+__device__ __forceinline__ void count_pairs(const int32_t* __restrict__ idx, int64_t p_begin, int64_t p_end, int k,
+                                            int N, int32_t* hist) {
+    constexpr int kBatch = 8;
+    for (int64_t p0 = p_begin + threadIdx.x; p0 < p_end; p0 += (int64_t)kThreads * kBatch) {
+        int32_t e[kBatch];
+#pragma unroll
+        for (int i = 0; i < kBatch; ++i) {
+            const int64_t p = p0 + (int64_t)i * kThreads;
+            e[i] = p < p_end ? idx[p] : -1;
+        }
+#pragma unroll
+        for (int i = 0; i < kBatch; ++i) {
+            const int64_t p = p0 + (int64_t)i * kThreads;
+            if (e[i] >= 0 && e[i] < N) atomicAdd(&hist[(int)(p % k) * N + e[i]], 1);
+        }
+    }
+}
+
 __global__ __launch_bounds__(kThreads) void dispatch_count_kernel(
     const int32_t* __restrict__ idx, int64_t S, int N, int k, int n_ct, int32_t* __restrict__ tile_count) {
     __shared__ int32_t hist[TAMOE_MAX_K * TAMOE_MAX_EXPERTS];
@@ -33,15 +54,47 @@ __global__ __launch_bounds__(kThreads) void dispatch_count_kernel(
     const int64_t p_begin = (int64_t)ct * kCountTile * k;
     int64_t p_end = p_begin + (int64_t)kCountTile * k;
     if (p_end > S * k) p_end = S * k;
-    for (int64_t p = p_begin + threadIdx.x; p < p_end; p += kThreads) {
-        const int e = idx[p];
-        const int j = (int)(p % k);
-        if (e >= 0 && e < N) atomicAdd(&hist[j * N + e], 1);
-    }
+    count_pairs(idx, p_begin, p_end, k, N, hist);
     __syncthreads();
     for (int q = threadIdx.x; q < k * N; q += kThreads) {
         const int j = q / N, e = q - j * N;
         tile_count[((size_t)j * n_ct + ct) * N + e] = hist[q];
+    }
+}
+
+// Exclusive prefix sum of v[0..n) (n <= 128) into out[0..n], out[n] = total.  Called by every
+// thread of the workgroup (at least 128 threads); tmp is 256 ints of LDS; v, out, tmp in LDS.
+__device__ __forceinline__ void exclusive_scan_128(const int32_t* v, int32_t* out, int32_t* tmp, int n) {
+    const int t = threadIdx.x;
+    const int32_t mine = (t < n) ? v[t] : 0;
+    if (t < 128) tmp[t] = mine;
+    __syncthreads();
+    int cur = 0;
+#pragma unroll
+    for (int s = 1; s < 128; s <<= 1) {
+        if (t < 128) tmp[(cur ^ 1) * 128 + t] = tmp[cur * 128 + t] + (t >= s ? tmp[cur * 128 + t - s] : 0);
+        __syncthreads();
+        cur ^= 1;
+    }
+    if (t < n) {
+        const int32_t incl = tmp[cur * 128 + t];
+        out[t] = incl - mine;
+        if (t == n - 1) out[n] = incl;
+    }
+    if (n == 0 && t == 0) out[0] = 0;
+    __syncthreads();
+}
+
+// kept rows per expert -> the three size outputs of tamoe_dispatch (kept and off in LDS)
+__device__ __forceinline__ void write_sizes(const int32_t* kept, const int32_t* off, int N, int P,
+                                            int32_t* __restrict__ kept_expert, int32_t* __restrict__ expert_offset,
+                                            int32_t* __restrict__ send_count_dev) {
+    const int t = threadIdx.x;
+    if (t < N) kept_expert[t] = kept[t];
+    if (t <= N) expert_offset[t] = off[t];
+    if (t < P) {
+        const int E = N / P;
+        send_count_dev[t] = off[(t + 1) * E] - off[t * E];
     }
 }
 
@@ -56,47 +109,66 @@ __global__ __launch_bounds__(kScanThreads) void dispatch_scan_kernel(
     int32_t* __restrict__ send_count_dev) {
     __shared__ int32_t part_sum[kScanParts][TAMOE_MAX_EXPERTS];
     __shared__ int32_t kept[TAMOE_MAX_EXPERTS];
+    __shared__ int32_t off[TAMOE_MAX_EXPERTS + 1];
+    __shared__ int32_t tmp[2 * 128];
     const int e = threadIdx.x % TAMOE_MAX_EXPERTS;
     const int part = threadIdx.x / TAMOE_MAX_EXPERTS;
     const int per_part = (n_entries + kScanParts - 1) / kScanParts;
     const int q0 = part * per_part;
     const int q1 = min(n_entries, q0 + per_part);
+    // Loads are issued in batches of kBatch (a loop that adds each value as it arrives would pay
+    // one L2 round trip per entry); the first batch stays in registers for the second pass.
+    constexpr int kBatch = 16;
+    int32_t first[kBatch];
     int32_t sum = 0;
-    if (e < N)
-        for (int q = q0; q < q1; ++q) sum += tile_count[(size_t)q * N + e];
+    if (e < N) {
+#pragma unroll
+        for (int i = 0; i < kBatch; ++i) first[i] = (q0 + i < q1) ? tile_count[(size_t)(q0 + i) * N + e] : 0;
+#pragma unroll
+        for (int i = 0; i < kBatch; ++i) sum += first[i];
+        for (int q = q0 + kBatch; q < q1; q += kBatch) {
+            int32_t v[kBatch];
+#pragma unroll
+            for (int i = 0; i < kBatch; ++i) v[i] = (q + i < q1) ? tile_count[(size_t)(q + i) * N + e] : 0;
+#pragma unroll
+            for (int i = 0; i < kBatch; ++i) sum += v[i];
+        }
+    }
     part_sum[part][e] = sum;
     __syncthreads();
     if (e < N) {
         int32_t run = 0;
         for (int pp = 0; pp < part; ++pp) run += part_sum[pp][e];
-        for (int q = q0; q < q1; ++q) {
-            const int32_t v = tile_count[(size_t)q * N + e];
-            tile_count[(size_t)q * N + e] = run;
-            run += v;
+#pragma unroll
+        for (int i = 0; i < kBatch; ++i) {
+            if (q0 + i < q1) tile_count[(size_t)(q0 + i) * N + e] = run;
+            run += first[i];
+        }
+        for (int q = q0 + kBatch; q < q1; q += kBatch) {
+            int32_t v[kBatch];
+#pragma unroll
+            for (int i = 0; i < kBatch; ++i) v[i] = (q + i < q1) ? tile_count[(size_t)(q + i) * N + e] : 0;
+#pragma unroll
+            for (int i = 0; i < kBatch; ++i) {
+                if (q + i < q1) tile_count[(size_t)(q + i) * N + e] = run;
+                run += v[i];
+            }
         }
         if (part == 0) {
             int32_t total = 0;
+#pragma unroll
             for (int pp = 0; pp < kScanParts; ++pp) total += part_sum[pp][e];
             const int32_t c = cap[e] < 0 ? 0 : cap[e];
             kept[e] = total < c ? total : c;
         }
     }
     __syncthreads();
-    if (part == 0 && e < N) {
-        int32_t off = 0;
-        for (int ee = 0; ee < e; ++ee) off += kept[ee];
-        kept_expert[e] = kept[e];
-        expert_offset[e] = off;
-        if (e == N - 1) expert_offset[N] = off + kept[e];
-    }
-    if (part == 1 && e < P) {
-        const int E = N / P;
-        int32_t rows = 0;
-        for (int ee = e * E; ee < (e + 1) * E; ++ee) rows += kept[ee];
-        send_count_dev[e] = rows;
-    }
+    exclusive_scan_128(kept, off, tmp, N);
+    write_sizes(kept, off, N, P, kept_expert, expert_offset, send_count_dev);
 }
 
+// One workgroup per 64 tokens: recounts the pairs of its count tile that precede them, ranks
+// their own pairs and writes slot[].
 __global__ __launch_bounds__(kThreads) void dispatch_slot_kernel(
     const int32_t* __restrict__ idx, const int32_t* __restrict__ cap, const int32_t* __restrict__ tile_base,
     const int32_t* __restrict__ expert_offset, int64_t S, int N, int k, int n_ct, int32_t* __restrict__ slot) {
@@ -113,11 +185,7 @@ __global__ __launch_bounds__(kThreads) void dispatch_slot_kernel(
     for (int p = threadIdx.x; p < pairs; p += kThreads) s_idx[p] = idx[t0 * k + p];
     __syncthreads();
     // pairs of this count tile that come before these tokens (same choice j)
-    for (int64_t p = tile_begin * k + threadIdx.x; p < t0 * k; p += kThreads) {
-        const int e = idx[p];
-        const int j = (int)(p % k);
-        if (e >= 0 && e < N) atomicAdd(&before[j * N + e], 1);
-    }
+    count_pairs(idx, tile_begin * k, t0 * k, k, N, before);
     __syncthreads();
     for (int p = threadIdx.x; p < pairs; p += kThreads) {
         const int e = s_idx[p];
