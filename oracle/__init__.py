@@ -59,6 +59,9 @@ def _load():
         "orc_slots": (c_i64, [c_vp, c_vp, c_i64, c_i32, c_i32, c_i32, c_vp, c_vp, c_vp, c_vp]),
         "orc_scatter": (None, [c_vp, c_i32, c_vp, c_i64, c_i32, c_i32, c_vp]),
         "orc_combine": (None, [c_vp, c_i32, c_vp, c_vp, c_i64, c_i32, c_i32, c_vp, c_vp]),
+        "orc_gate_bwd": (None, [c_vp, c_vp, c_vp, c_vp, c_vp, c_dbl, c_i64, c_i32, c_i32, c_i32, c_vp]),
+        "orc_combine_bwd": (None, [c_vp, c_vp, c_i32, c_vp, c_vp, c_i64, c_i64, c_i32, c_i32, c_vp, c_vp, c_vp]),
+        "orc_dispatch_bwd": (None, [c_vp, c_i32, c_vp, c_i64, c_i32, c_i32, c_vp, c_vp]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(lib, name)
@@ -237,6 +240,48 @@ def combine(recv, dtype: int, slot, wgt, want_exact: bool = True, want_rounded: 
     y = np.empty((S, d), dtype=recv.dtype) if want_rounded else None
     _load().orc_combine(_p(recv), dtype, _p(slot), _p(wgt), S, d, k, _p(y_exact), _p(y))
     return y_exact, y
+
+
+# ---- backward -----------------------------------------------------------------
+
+def gate_bwd(lg, idx, dwgt, p, c, loss_scale: float, P: int) -> np.ndarray:
+    lg = _c(lg, np.float64)
+    idx = _c(idx, np.int32)
+    dwgt = _c(dwgt, np.float64)
+    c = _c(c, np.int32)
+    p = None if p is None else _c(p, np.float64)
+    S, N = lg.shape
+    k = idx.shape[1]
+    out = np.empty((S, N), dtype=np.float64)
+    _load().orc_gate_bwd(_p(lg), _p(idx), _p(dwgt), _p(p), _p(c), float(loss_scale), S, N, P, k, _p(out))
+    return out
+
+
+def combine_bwd(dy, recv, dtype: int, slot, wgt, want_rounded: bool = True):
+    dy = _storage(dy, dtype)
+    recv = _storage(recv, dtype)
+    slot = _c(slot, np.int32)
+    wgt = _c(wgt, np.float64)
+    S, k = slot.shape
+    K, d = recv.shape
+    assert dy.shape == (S, d)
+    drecv_exact = np.empty((K, d), dtype=np.float64)
+    drecv = np.empty((K, d), dtype=recv.dtype) if want_rounded else None
+    dwgt = np.empty((S, k), dtype=np.float64)
+    _load().orc_combine_bwd(_p(dy), _p(recv), dtype, _p(slot), _p(wgt), S, K, d, k, _p(drecv_exact), _p(drecv),
+                            _p(dwgt))
+    return drecv_exact, drecv, dwgt
+
+
+def dispatch_bwd(dsend, dtype: int, slot, want_rounded: bool = True):
+    dsend = _storage(dsend, dtype)
+    slot = _c(slot, np.int32)
+    S, k = slot.shape
+    d = dsend.shape[1]
+    dx_exact = np.empty((S, d), dtype=np.float64)
+    dx = np.empty((S, d), dtype=dsend.dtype) if want_rounded else None
+    _load().orc_dispatch_bwd(_p(dsend), dtype, _p(slot), S, d, k, _p(dx_exact), _p(dx))
+    return dx_exact, dx
 
 
 # ---- whole path (the steps above, in the paper's order) -----------------------

@@ -411,3 +411,100 @@ void orc_combine(const void *recv, int dtype, const int32_t *slot, const double 
         }
     }
 }
+
+/* ---- backward of the path (for training: the auxiliary loss is added to the train loss,
+ * Section 3.1 / Section 4.3, so its gradient and the transposes of the row movers are needed) -- */
+
+/*
+ * Gradient with respect to the gate scores, for fixed routing (the counts c and the selected
+ * indices do not depend on the scores differentiably):
+ *   L = sum_{t,j} dwgt[t][j] * G[t][idx[t][j]]  +  loss_scale * l_topo,
+ *   l_topo = N*P * sum_e p[e] * m[e] * c[e] / S,   m[e] = (1/S) sum_t G[t][e]   (Section 4.3).
+ * With u[t][e] = sum_j dwgt[t][j] * [idx[t][j] == e] + loss_scale * N*P*p[e]*c[e]/S^2 the softmax
+ * Jacobian dG_i/dl_e = G_i (delta_ie - G_e) gives
+ *   dlogits[t][e] = G[t][e] * ( u[t][e] - sum_e' u[t][e'] * G[t][e'] ).
+ * p == NULL stands for the load-balance loss l_aux of Section 3.1 (weights 1, no N*P factor).
+ */
+void orc_gate_bwd(const double *logits, const int32_t *idx, const double *dwgt, const double *p,
+                  const int32_t *c, double loss_scale, int64_t S, int N, int P, int k, double *dlogits)
+{
+    double *G = (double *)malloc((size_t)S * N * sizeof(double));
+    orc_softmax(logits, S, N, G);
+#pragma omp parallel for num_threads(g_threads) schedule(static)
+    for (int64_t t = 0; t < S; ++t) {
+        double ubar = 0.0;
+        for (int e = 0; e < N; ++e) {
+            double u = loss_scale * (p ? (double)N * (double)P * p[e] : 1.0) * (double)c[e]
+                       / ((double)S * (double)S);
+            for (int j = 0; j < k; ++j)
+                if (idx[t * k + j] == e)
+                    u += dwgt[t * k + j];
+            dlogits[t * N + e] = u; /* u for now */
+            ubar += u * G[t * N + e];
+        }
+        for (int e = 0; e < N; ++e)
+            dlogits[t * N + e] = G[t * N + e] * (dlogits[t * N + e] - ubar);
+    }
+    free(G);
+}
+
+/*
+ * Backward of the combine y[t] = sum_j wgt[t][j] * recv[slot[t][j]]:
+ *   drecv[slot[t][j]][:] = wgt[t][j] * dy[t][:]          for every kept pair (rows that no slot
+ *                                                         names stay zero),
+ *   dwgt[t][j] = sum_q dy[t][q] * recv[slot[t][j]][q]    for a kept pair, 0 for a dropped one.
+ * drecv_exact (may be NULL) is the double result, drecv (may be NULL) the result rounded once
+ * to the storage type.
+ */
+void orc_combine_bwd(const void *dy, const void *recv, int dtype, const int32_t *slot,
+                     const double *wgt, int64_t S, int64_t K, int d, int k,
+                     double *drecv_exact, void *drecv, double *dwgt)
+{
+    if (drecv_exact)
+        memset(drecv_exact, 0, (size_t)K * d * sizeof(double));
+    if (drecv)
+        memset(drecv, 0, (size_t)K * d * elem_size(dtype));
+#pragma omp parallel for num_threads(g_threads) schedule(static)
+    for (int64_t t = 0; t < S; ++t) {
+        for (int j = 0; j < k; ++j) {
+            int32_t s = slot[t * k + j];
+            double dot = 0.0;
+            if (s >= 0) {
+                for (int q = 0; q < d; ++q) {
+                    double g = load_elem(dy, dtype, t * d + q);
+                    double v = wgt[t * k + j] * g;
+                    if (drecv_exact)
+                        drecv_exact[(int64_t)s * d + q] = v;
+                    if (drecv)
+                        store_elem(drecv, dtype, (int64_t)s * d + q, v);
+                    dot += g * load_elem(recv, dtype, (int64_t)s * d + q);
+                }
+            }
+            dwgt[t * k + j] = dot;
+        }
+    }
+}
+
+/*
+ * Backward of the scatter send[slot[t][j]] = x[t]: the transpose adds the rows back,
+ *   dx[t][:] = sum over kept j of dsend[slot[t][j]][:].
+ */
+void orc_dispatch_bwd(const void *dsend, int dtype, const int32_t *slot, int64_t S, int d, int k,
+                      double *dx_exact, void *dx)
+{
+#pragma omp parallel for num_threads(g_threads) schedule(static)
+    for (int64_t t = 0; t < S; ++t) {
+        for (int q = 0; q < d; ++q) {
+            double acc = 0.0;
+            for (int j = 0; j < k; ++j) {
+                int32_t s = slot[t * k + j];
+                if (s >= 0)
+                    acc += load_elem(dsend, dtype, (int64_t)s * d + q);
+            }
+            if (dx_exact)
+                dx_exact[t * d + q] = acc;
+            if (dx)
+                store_elem(dx, dtype, t * d + q, acc);
+        }
+    }
+}
