@@ -169,6 +169,42 @@ int tamoe_combine(const void* recv, int64_t K_rows, const int32_t* slot, const f
                   int dtype, int64_t S, int d, int k, void* y, void* stream);
 
 /*
+ * Backward of the path (training adds the auxiliary loss to the train loss, Sections 3.1 and 4.3,
+ * so its gradient and the transposes of the two row movers are needed).  Routing is fixed: the
+ * selected indices, the counts and the slots are constants of the differentiation.
+ *
+ * tamoe_gate_bwd: gradient to the gate scores.  With L = sum_{t,j} d_topk_w[t][j] * G[t][idx[t][j]]
+ * + loss_scale * l_topo (penalty != NULL; l_aux if penalty == NULL) and the softmax Jacobian,
+ *   u[t][e]        = sum_j d_topk_w[t][j] * [topk_idx[t][j] == e] + loss_scale * N*P * penalty[e] * c_expert[e] / S^2
+ *   d_logits[t][e] = G[t][e] * ( u[t][e] - sum_e' u[t][e'] * G[t][e'] ),     G = softmax(logits[t][:])
+ * (for l_aux: the factor N*P*penalty[e] is 1).  logits [S,N] float, topk_idx [S,k], d_topk_w [S,k]
+ * float, penalty [N] float or NULL, c_expert [N]: device inputs; d_logits [S,N] float: device out.
+ */
+int tamoe_gate_bwd(const float* logits, const int32_t* topk_idx, const float* d_topk_w,
+                   const float* penalty, const int32_t* c_expert, float loss_scale,
+                   int64_t S, int N, int P, int k, float* d_logits, void* stream);
+
+/*
+ * tamoe_combine_bwd: transpose of tamoe_combine for an upstream gradient dy [S,d] (`dtype`):
+ *   d_recv[slot[t][j]][:] = topk_w[t][j] * dy[t][:]              rounded once to `dtype`, kept pairs
+ *   d_topk_w[t][j]        = sum_q dy[t][q] * recv[slot[t][j]][q] fp32, 0 for a dropped pair
+ * Every row of the send buffer is named by exactly one kept pair, so rows 0..K-1 of d_recv are
+ * all written; rows that no slot names are left untouched.  dy [S,d], recv [K_rows,d], slot [S,k],
+ * topk_w [S,k]: device inputs; d_recv [K_rows,d] `dtype`, d_topk_w [S,k] float: device outputs.
+ */
+int tamoe_combine_bwd(const void* dy, const void* recv, int64_t K_rows, const int32_t* slot,
+                      const float* topk_w, int dtype, int64_t S, int d, int k,
+                      void* d_recv, float* d_topk_w, void* stream);
+
+/*
+ * tamoe_dispatch_bwd: transpose of the scatter of tamoe_dispatch for the gradient d_send [K_rows,d]
+ * that arrives at the send buffer:  d_x[t][:] = sum over kept j of d_send[slot[t][j]][:], fp32
+ * accumulation, one rounding to `dtype`; zero row for a token with no kept choice.
+ */
+int tamoe_dispatch_bwd(const void* d_send, int64_t K_rows, const int32_t* slot, int dtype,
+                       int64_t S, int d, int k, void* d_x, void* stream);
+
+/*
  * Kernel timing aid for benchmarks (not a step of the path; off unless started).
  * tamoe_trace_start creates 2*max_launches HIP events on the current device; from then on every
  * kernel the device functions above enqueue is bracketed by a pair of events on its stream,

@@ -32,6 +32,7 @@ OK, INVALID_ARG, UNSUPPORTED, WORKSPACE_TOO_SMALL, HIP_ERROR = 0, 1, 2, 3, 4
 EXPORTS = (
     "tamoe_version", "tamoe_last_error", "tamoe_topo_pattern", "tamoe_workspace_bytes",
     "tamoe_gate", "tamoe_select", "tamoe_aux_loss", "tamoe_dispatch", "tamoe_combine",
+    "tamoe_gate_bwd", "tamoe_combine_bwd", "tamoe_dispatch_bwd",
     "tamoe_trace_start", "tamoe_trace_filter", "tamoe_trace_stop", "tamoe_trace_get", "tamoe_trace_clear", "tamoe_copy_probe", "tamoe_mix_probe",
 )
 
@@ -73,6 +74,12 @@ def lib() -> ctypes.CDLL:
     L.tamoe_dispatch.argtypes = [vp, vp, vp, i32, i64, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, sz, vp]
     L.tamoe_combine.restype = i32
     L.tamoe_combine.argtypes = [vp, i64, vp, vp, i32, i64, i32, i32, vp, vp]
+    L.tamoe_gate_bwd.restype = i32
+    L.tamoe_gate_bwd.argtypes = [vp, vp, vp, vp, vp, ctypes.c_float, i64, i32, i32, i32, vp, vp]
+    L.tamoe_combine_bwd.restype = i32
+    L.tamoe_combine_bwd.argtypes = [vp, vp, i64, vp, vp, i32, i64, i32, i32, vp, vp, vp]
+    L.tamoe_dispatch_bwd.restype = i32
+    L.tamoe_dispatch_bwd.argtypes = [vp, i64, vp, i32, i64, i32, i32, vp, vp]
     L.tamoe_trace_start.restype = i32
     L.tamoe_trace_start.argtypes = [i32]
     L.tamoe_trace_filter.restype = i32
@@ -217,6 +224,40 @@ def tamoe_combine(recv, K_rows: int, slot, topk_w, y, stream=None) -> None:
     _check(lib().tamoe_combine(
         _dev(recv, None, "recv"), K_rows, _dev(slot, torch.int32, "slot"),
         _dev(topk_w, torch.float32, "topk_w"), _dtype_code(y), S, d, k, _dev(y, None, "y"), _stream(stream)))
+
+
+def tamoe_gate_bwd(logits, topk_idx, d_topk_w, penalty, c_expert, loss_scale: float, P: int, d_logits,
+                   stream=None) -> None:
+    S, N = logits.shape
+    k = topk_idx.shape[1]
+    _check(lib().tamoe_gate_bwd(
+        _dev(logits, torch.float32, "logits"), _dev(topk_idx, torch.int32, "topk_idx"),
+        _dev(d_topk_w, torch.float32, "d_topk_w"), _dev(penalty, torch.float32, "penalty"),
+        _dev(c_expert, torch.int32, "c_expert"), float(loss_scale), S, N, P, k,
+        _dev(d_logits, torch.float32, "d_logits"), _stream(stream)))
+
+
+def tamoe_combine_bwd(dy, recv, K_rows: int, slot, topk_w, d_recv, d_topk_w, stream=None) -> None:
+    S, k = slot.shape
+    d = dy.shape[1]
+    if recv is not None and (recv.dtype != dy.dtype or recv.numel() < K_rows * d):
+        raise TamoeError(INVALID_ARG, "recv must have the dtype of dy and hold K_rows rows")
+    if d_recv is not None and (d_recv.dtype != dy.dtype or d_recv.numel() < K_rows * d):
+        raise TamoeError(INVALID_ARG, "d_recv must have the dtype of dy and hold K_rows rows")
+    _check(lib().tamoe_combine_bwd(
+        _dev(dy, None, "dy"), _dev(recv, None, "recv"), K_rows, _dev(slot, torch.int32, "slot"),
+        _dev(topk_w, torch.float32, "topk_w"), _dtype_code(dy), S, d, k, _dev(d_recv, None, "d_recv"),
+        _dev(d_topk_w, torch.float32, "d_topk_w"), _stream(stream)))
+
+
+def tamoe_dispatch_bwd(d_send, K_rows: int, slot, d_x, stream=None) -> None:
+    S, k = slot.shape
+    d = d_x.shape[1]
+    if d_send is not None and (d_send.dtype != d_x.dtype or d_send.numel() < K_rows * d):
+        raise TamoeError(INVALID_ARG, "d_send must have the dtype of d_x and hold K_rows rows")
+    _check(lib().tamoe_dispatch_bwd(
+        _dev(d_send, None, "d_send"), K_rows, _dev(slot, torch.int32, "slot"), _dtype_code(d_x), S, d, k,
+        _dev(d_x, None, "d_x"), _stream(stream)))
 
 
 def tamoe_trace_start(max_launches: int) -> None:

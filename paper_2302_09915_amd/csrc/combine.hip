@@ -6,59 +6,18 @@
 // ascending j with one fused multiply-add per term, rounds once to the storage type and writes
 // the chunk of y.  Bound by HBM: d*b bytes read per kept pair, d*b written per token; the HBM
 // latency is covered by the number of independent wavefronts, as in a plain copy.
+#include "chunk.h"
 #include "internal.h"
 
 namespace tamoe {
 
 constexpr int kThreads = 256;
 
-template <int DT>
-struct Chunk;
-
-template <>
-struct Chunk<TAMOE_F32> {
-    static constexpr int kElems = 4;
-    static __device__ __forceinline__ void fma(float (&acc)[8], float w, vec16 v) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i) acc[i] = __builtin_fmaf(w, __uint_as_float(v[i]), acc[i]);
-    }
-    static __device__ __forceinline__ vec16 pack(const float (&acc)[8]) {
-        vec16 r;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) r[i] = __float_as_uint(acc[i]);
-        return r;
-    }
-};
-
-// fp32 -> bfloat16, round to nearest, ties to even (finite inputs; NaN stays NaN)
-__device__ __forceinline__ uint32_t f32_to_bf16(float f) {
-    uint32_t u = __float_as_uint(f);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;
-    return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
-}
-
-template <>
-struct Chunk<TAMOE_BF16> {
-    static constexpr int kElems = 8;
-    static __device__ __forceinline__ void fma(float (&acc)[8], float w, vec16 v) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            acc[2 * i] = __builtin_fmaf(w, __uint_as_float(v[i] << 16), acc[2 * i]);
-            acc[2 * i + 1] = __builtin_fmaf(w, __uint_as_float(v[i] & 0xffff0000u), acc[2 * i + 1]);
-        }
-    }
-    static __device__ __forceinline__ vec16 pack(const float (&acc)[8]) {
-        vec16 r;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) r[i] = f32_to_bf16(acc[2 * i]) | (f32_to_bf16(acc[2 * i + 1]) << 16);
-        return r;
-    }
-};
-
 // KK > 0: k is the compile-time constant KK; KK == 0: any k up to TAMOE_MAX_K.
 // ROWU: a row is a multiple of 1 KiB, so the 64 chunks of a wavefront belong to one token and
 // its slots and weights are read once per wavefront through the scalar unit.
-template <int DT, int KK, int U, bool ROWU>
+// UNITW: every weight is 1 (the transpose of the scatter: dx[t] = sum of the rows its slots name).
+template <int DT, int KK, int U, bool ROWU, bool UNITW>
 __global__ __launch_bounds__(kThreads) void combine_kernel(const vec16* __restrict__ recv, int64_t K_rows,
                                                            const int32_t* __restrict__ slot,
                                                            const float* __restrict__ topk_w, int64_t total_chunks,
@@ -82,7 +41,7 @@ __global__ __launch_bounds__(kThreads) void combine_kernel(const vec16* __restri
             for (int j = 0; j < KM; ++j) {
                 if (j < k) {
                     const int32_t s = slot[(int64_t)t * k + j];
-                    wgt[u][j] = topk_w[(int64_t)t * k + j];
+                    wgt[u][j] = UNITW ? 1.0f : topk_w[(int64_t)t * k + j];
                     use[u][j] = s >= 0 && (int64_t)s < K_rows;
                     if (use[u][j]) v[u][j] = __builtin_nontemporal_load(recv + (size_t)s * cpr + col);
                 }
@@ -109,16 +68,25 @@ static void launch_combine_k(const void* recv, int64_t K_rows, const int32_t* sl
     const vec16* r = static_cast<const vec16*>(recv);
     vec16* out = static_cast<vec16*>(y);
     const int shift = pow2_shift(cpr);
-    if (cpr % 64 == 0)
-        combine_kernel<DT, KK, U, true><<<grid, block, 0, st>>>(r, K_rows, slot, topk_w, total, k, cpr, shift, out);
-    else
-        combine_kernel<DT, KK, U, false><<<grid, block, 0, st>>>(r, K_rows, slot, topk_w, total, k, cpr, shift, out);
+    const bool rowu = cpr % 64 == 0;
+    if (topk_w != nullptr) {
+        if (rowu)
+            combine_kernel<DT, KK, U, true, false><<<grid, block, 0, st>>>(r, K_rows, slot, topk_w, total, k, cpr, shift, out);
+        else
+            combine_kernel<DT, KK, U, false, false><<<grid, block, 0, st>>>(r, K_rows, slot, topk_w, total, k, cpr, shift, out);
+    } else {
+        if (rowu)
+            combine_kernel<DT, KK, U, true, true><<<grid, block, 0, st>>>(r, K_rows, slot, topk_w, total, k, cpr, shift, out);
+        else
+            combine_kernel<DT, KK, U, false, true><<<grid, block, 0, st>>>(r, K_rows, slot, topk_w, total, k, cpr, shift, out);
+    }
 }
 
+// topk_w == nullptr: unit weights (tamoe_dispatch_bwd)
 template <int DT>
 static void launch_combine(const void* recv, int64_t K_rows, const int32_t* slot, const float* topk_w, int64_t S,
                            int k, int cpr, void* y, hipStream_t st) {
-    TraceScope tr("combine_kernel", st);
+    TraceScope tr(topk_w != nullptr ? "combine_kernel" : "dispatch_bwd_kernel", st);
     if (k == 1)
         launch_combine_k<DT, 1, 2>(recv, K_rows, slot, topk_w, S, k, cpr, y, st);
     else if (k == 2)
@@ -131,9 +99,8 @@ static void launch_combine(const void* recv, int64_t K_rows, const int32_t* slot
 
 using namespace tamoe;
 
-extern "C" int tamoe_combine(const void* recv, int64_t K_rows, const int32_t* slot, const float* topk_w, int dtype,
-                             int64_t S, int d, int k, void* y, void* stream) {
-    const char* fn = "tamoe_combine";
+static int combine_entry(const char* fn, const void* recv, int64_t K_rows, const int32_t* slot, const float* topk_w,
+                         bool weighted, int dtype, int64_t S, int d, int k, void* y, void* stream) {
     clear_error();
     int rc;
     if (S < 0 || K_rows < 0) return fail(TAMOE_INVALID_ARG, "%s: S and K_rows must not be negative", fn);
@@ -142,17 +109,27 @@ extern "C" int tamoe_combine(const void* recv, int64_t K_rows, const int32_t* sl
     if (S * (int64_t)k >= (int64_t)1 << 31) return fail(TAMOE_UNSUPPORTED, "%s: S*k does not fit int32", fn);
     if ((rc = check_rows(fn, dtype, d)) != TAMOE_OK) return rc;
     if (S == 0) return TAMOE_OK;
-    if (K_rows > 0 && (rc = check_ptr(fn, "recv", recv, 16)) != TAMOE_OK) return rc;
+    if (K_rows > 0 && (rc = check_ptr(fn, weighted ? "recv" : "d_send", recv, 16)) != TAMOE_OK) return rc;
     if ((rc = check_ptr(fn, "slot", slot, 4)) != TAMOE_OK) return rc;
-    if ((rc = check_ptr(fn, "topk_w", topk_w, 4)) != TAMOE_OK) return rc;
-    if ((rc = check_ptr(fn, "y", y, 16)) != TAMOE_OK) return rc;
+    if (weighted && (rc = check_ptr(fn, "topk_w", topk_w, 4)) != TAMOE_OK) return rc;
+    if ((rc = check_ptr(fn, weighted ? "y" : "d_x", y, 16)) != TAMOE_OK) return rc;
     const int cpr = d * elem_bytes(dtype) / 16;  // 16-byte chunks per row
     if (ceil_div(S * (int64_t)cpr, kThreads * 1) > 0x7fffffff)
-        return fail(TAMOE_UNSUPPORTED, "%s: y is too large for one launch", fn);
+        return fail(TAMOE_UNSUPPORTED, "%s: the output is too large for one launch", fn);
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (dtype == TAMOE_F32)
-        launch_combine<TAMOE_F32>(recv, K_rows, slot, topk_w, S, k, cpr, y, st);
+        launch_combine<TAMOE_F32>(recv, K_rows, slot, weighted ? topk_w : nullptr, S, k, cpr, y, st);
     else
-        launch_combine<TAMOE_BF16>(recv, K_rows, slot, topk_w, S, k, cpr, y, st);
+        launch_combine<TAMOE_BF16>(recv, K_rows, slot, weighted ? topk_w : nullptr, S, k, cpr, y, st);
     return check_launch(fn, "combine_kernel");
+}
+
+extern "C" int tamoe_combine(const void* recv, int64_t K_rows, const int32_t* slot, const float* topk_w, int dtype,
+                             int64_t S, int d, int k, void* y, void* stream) {
+    return combine_entry("tamoe_combine", recv, K_rows, slot, topk_w, true, dtype, S, d, k, y, stream);
+}
+
+extern "C" int tamoe_dispatch_bwd(const void* d_send, int64_t K_rows, const int32_t* slot, int dtype, int64_t S, int d,
+                                  int k, void* d_x, void* stream) {
+    return combine_entry("tamoe_dispatch_bwd", d_send, K_rows, slot, nullptr, false, dtype, S, d, k, d_x, stream);
 }
