@@ -41,6 +41,7 @@ def parse_args():
     ap.add_argument("--workload", default="large")
     ap.add_argument("--cap-mode", type=int, default=0, help="0 uniform capacity, 1 proportional to the target pattern")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-backward", action="store_true", help="skip the (untimed) measurement of the backward kernels")
     ap.add_argument("--no-trace", action="store_true",
                     help="no HIP events inside the timed region (per-kernel times then come from an extra traced pass)")
     ap.add_argument("--graph", action="store_true",
@@ -237,6 +238,47 @@ def main():
     T.tamoe_trace_filter(None)
     T.tamoe_trace_clear()
 
+    # Backward kernels (the next row of the scope after the forward path): measured in a pass of
+    # their own with events around every launch; they are not part of `value`.
+    backward = None
+    if not args.no_backward:
+        K_now = int(off[-1].item())
+        logits = torch.empty((S, N), dtype=f32, device=dev)
+        T.tamoe_gate(x, w, P, k, logits, topk_idx, topk_w, m, c_expert, c_device, ws, None)
+        dy = y                                   # any tensor of the shape of y serves as upstream gradient
+        d_recv = torch.empty((max(K_now, 1), d), dtype=x.dtype, device=dev)
+        d_w = torch.empty((S, k), dtype=f32, device=dev)
+        d_logits = torch.empty((S, N), dtype=f32, device=dev)
+        d_x = torch.empty((S, d), dtype=x.dtype, device=dev)
+
+        def bwd():
+            T.tamoe_combine_bwd(dy, send, K_now, slot, topk_w, d_recv, d_w, None)
+            T.tamoe_gate_bwd(logits, topk_idx, d_w, pen_d, c_expert, 1.0, P, d_logits, None)
+            T.tamoe_dispatch_bwd(d_recv, K_now, slot, d_x, None)
+
+        for _ in range(3):
+            bwd()
+        torch.cuda.synchronize()
+        reps = 10
+        T.tamoe_trace_start(3 * reps)
+        for _ in range(reps):
+            bwd()
+        torch.cuda.synchronize()
+        rec = collect()
+        T.tamoe_trace_clear()
+        live_b = int((slot >= 0).any(dim=1).sum().item())
+        rowb = d * b
+        bwd_bytes = {"combine_bwd_kernel": S * rowb + 2 * K_now * rowb + S * k * 12,
+                     "gate_bwd_kernel": 2 * S * N * 4 + S * k * 8,
+                     "dispatch_bwd_kernel": K_now * rowb + S * rowb + S * k * 4}
+        backward = []
+        for name, ts in rec.items():
+            us = float(np.mean(ts)) * 1e3
+            gbs = bwd_bytes[name] / (us * 1e-6) / 1e9
+            backward.append({"kernel": name, "avg_us": round(us, 2), "algo_bytes": int(bwd_bytes[name]),
+                             "achieved_GBs": round(gbs, 1), "frac_of_hbm_peak": round(gbs / HBM_PEAK_GBS, 4)})
+        del logits, d_recv, d_w, d_logits, d_x
+
     ms_per_step = elapsed * 1e3 / args.steps
     tokens_per_s = S * args.steps / elapsed
 
@@ -300,6 +342,7 @@ def main():
                        "GBs": round(copy_gbs, 1), "frac_of_hbm_peak": round(copy_gbs / HBM_PEAK_GBS, 4)},
         "mix_probe": mix,
         "kernels": kernels,
+        "backward_kernels": backward,
         "l_topo": float(loss.item()),
         "mode": "graph replay" if args.graph else "eager",
         "kernels_table_from": f"untimed pass of {table_steps} steps with HIP events around every launch",

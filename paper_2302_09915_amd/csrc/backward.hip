@@ -15,7 +15,7 @@ namespace tamoe {
 constexpr int kThreads = 256;
 
 // ---- combine backward: one wavefront per token ------------------------------------------------
-// The wavefront walks its row of dy in steps of 64 chunks (1 KiB), two steps per batch: all loads
+// The wavefront walks its row of dy in steps of 64 chunks (1 KiB), four steps per batch: all loads
 // of a batch (dy and the k source rows of recv) are issued before anything is stored, because
 // stores and loads retire in one order and a store-then-load loop would wait for the stores.
 // d_w is a fixed-order sum: per lane over its chunks, then a butterfly over the lanes.
@@ -27,7 +27,7 @@ __global__ __launch_bounds__(kThreads) void combine_bwd_kernel(const vec16* __re
                                                                int cpr, vec16* __restrict__ d_recv,
                                                                float* __restrict__ d_w) {
     constexpr int KM = KK > 0 ? KK : TAMOE_MAX_K;
-    constexpr int UB = 2;
+    constexpr int UB = 4;
     const int k = KK > 0 ? KK : k_arg;
     const int lane = threadIdx.x & 63;
     const int64_t t64 = ((int64_t)blockIdx.x * kThreads + threadIdx.x) >> 6;
@@ -90,90 +90,114 @@ __global__ __launch_bounds__(kThreads) void combine_bwd_kernel(const vec16* __re
     }
 }
 
-// ---- gate backward: the accumulator layout of the gate's selection stage ----------------------
-__device__ __forceinline__ int expert_at(int nb, int v, int half) {
-    return nb * 32 + ((v >> 2) << 3) + (half << 2) + (v & 3);
+// ---- gate backward ------------------------------------------------------------------------------
+// value of lane (lane ^ MASK), MASK < 32, through the LDS crossbar
+template <int MASK>
+__device__ __forceinline__ float lane_xor(float v) {
+    return __int_as_float(__builtin_amdgcn_ds_swizzle(__float_as_int(v), (MASK << 10) | 0x1f));
+}
+template <int LPT>
+__device__ __forceinline__ float group_max(float v) {
+    if constexpr (LPT > 1) v = fmaxf(v, lane_xor<1>(v));
+    if constexpr (LPT > 2) v = fmaxf(v, lane_xor<2>(v));
+    if constexpr (LPT > 4) v = fmaxf(v, lane_xor<4>(v));
+    if constexpr (LPT > 8) v = fmaxf(v, lane_xor<8>(v));
+    if constexpr (LPT > 16) v = fmaxf(v, lane_xor<16>(v));
+    return v;
+}
+template <int LPT>
+__device__ __forceinline__ float group_sum(float v) {
+    if constexpr (LPT > 1) v += lane_xor<1>(v);
+    if constexpr (LPT > 2) v += lane_xor<2>(v);
+    if constexpr (LPT > 4) v += lane_xor<4>(v);
+    if constexpr (LPT > 8) v += lane_xor<8>(v);
+    if constexpr (LPT > 16) v += lane_xor<16>(v);
+    return v;
 }
 
-// One wavefront per 32 tokens; lane l holds, for token (l & 31), the experts expert_at(nb, v, l>>5),
-// and the lane pair (l, l^32) a token's whole score vector.
+// A token's score row is spread over LPT consecutive lanes, four consecutive experts per lane
+// (4*LPT >= N), so that a wavefront reads and writes whole rows contiguously; the three
+// reductions of a row (max, sum of exponentials, sum of u*G) are butterflies over those lanes.
 //   u[e]  = coef[e] + sum_j d_w[t][j] * [idx[t][j] == e],   coef[e] = scale * p[e] * c[e]
 //   dl[e] = G[e] * (u[e] - sum_e' u[e'] G[e'])
-template <int NB>
+// VEC: N is a multiple of 4, rows are 16-byte aligned and each lane moves one dwordx4.
+template <int LPT, bool VEC>
 __global__ __launch_bounds__(kThreads) void gate_bwd_kernel(const float* __restrict__ logits,
                                                             const int32_t* __restrict__ idx,
                                                             const float* __restrict__ d_w,
                                                             const float* __restrict__ penalty,
                                                             const int32_t* __restrict__ c, float scale, int64_t S,
                                                             int N, int k, float* __restrict__ d_logits) {
-    __shared__ float coef[NB * 32];
+    __shared__ float coef[TAMOE_MAX_EXPERTS + 4];
     const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6, half = lane >> 5;
-    for (int e = tid; e < NB * 32; e += kThreads)
+    for (int e = tid; e < TAMOE_MAX_EXPERTS + 4; e += kThreads)
         coef[e] = e < N ? scale * (penalty != nullptr ? penalty[e] : 1.0f) * (float)c[e] : 0.f;
     __syncthreads();
-    const int64_t token = ((int64_t)blockIdx.x * 4 + wave) * 32 + (lane & 31);
+    const int64_t token = ((int64_t)blockIdx.x * kThreads + tid) / LPT;
+    const int e0 = (tid % LPT) * 4;
     const bool token_ok = token < S;
     const int64_t tk = token_ok ? token : 0;
+    const float* row = logits + (size_t)tk * N;
 
-    int sel[TAMOE_MAX_K];
-    float dwt[TAMOE_MAX_K];
+    float l[4];
+    if (VEC) {
+        const float4 q = (token_ok && e0 < N) ? *reinterpret_cast<const float4*>(row + e0)
+                                             : make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
+        l[0] = q.x; l[1] = q.y; l[2] = q.z; l[3] = q.w;
+    } else {
 #pragma unroll
-    for (int j = 0; j < TAMOE_MAX_K; ++j) {
-        sel[j] = -1;
-        dwt[j] = 0.f;
-        if (j < k && token_ok) {
-            sel[j] = idx[tk * k + j];
-            dwt[j] = d_w[tk * k + j];
-        }
+        for (int i = 0; i < 4; ++i) l[i] = (token_ok && e0 + i < N) ? row[e0 + i] : -INFINITY;
     }
-    float sc[NB][16];
-    float mx = -INFINITY;
-#pragma unroll
-    for (int nb = 0; nb < NB; ++nb)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int e = expert_at(nb, v, half);
-            sc[nb][v] = (token_ok && e < N) ? logits[(size_t)tk * N + e] : -INFINITY;
-            mx = fmaxf(mx, sc[nb][v]);
-        }
-    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    float mx = group_max<LPT>(fmaxf(fmaxf(l[0], l[1]), fmaxf(l[2], l[3])));
     if (!token_ok) mx = 0.f;
-    float part = 0.f;
+    float g[4], part = 0.f;
 #pragma unroll
-    for (int nb = 0; nb < NB; ++nb)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            sc[nb][v] = __builtin_amdgcn_exp2f((sc[nb][v] - mx) * 1.44269504088896340736f);
-            part += sc[nb][v];
-        }
-    const float den = part + __shfl_xor(part, 32);
-    const float inv = token_ok ? 1.0f / den : 0.f;
-    float ubar = 0.f;
-    float u[NB][16];
-#pragma unroll
-    for (int nb = 0; nb < NB; ++nb)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int e = expert_at(nb, v, half);
-            float uu = coef[e];
-#pragma unroll
-            for (int j = 0; j < TAMOE_MAX_K; ++j)
-                if (j < k && sel[j] == e) uu += dwt[j];
-            sc[nb][v] *= inv;  // G
-            u[nb][v] = uu;
-            ubar = __builtin_fmaf(uu, sc[nb][v], ubar);
-        }
-    ubar += __shfl_xor(ubar, 32);
-    if (token_ok) {
-#pragma unroll
-        for (int nb = 0; nb < NB; ++nb)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int e = expert_at(nb, v, half);
-                if (e < N) d_logits[(size_t)token * N + e] = sc[nb][v] * (u[nb][v] - ubar);
-            }
+    for (int i = 0; i < 4; ++i) {
+        g[i] = __builtin_amdgcn_exp2f((l[i] - mx) * 1.44269504088896340736f);
+        part += g[i];
     }
+    const float den = group_sum<LPT>(part);
+    const float inv = token_ok ? 1.0f / den : 0.f;
+    float u[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        g[i] *= inv;
+        u[i] = coef[e0 + i];
+    }
+    for (int j = 0; j < k; ++j) {
+        const int sel = token_ok ? idx[tk * k + j] : -1;
+        const float dwt = token_ok ? d_w[tk * k + j] : 0.f;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) u[i] += (sel == e0 + i) ? dwt : 0.f;
+    }
+    float ub = 0.f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) ub = __builtin_fmaf(u[i], g[i], ub);
+    const float ubar = group_sum<LPT>(ub);
+    if (token_ok) {
+        float* out = d_logits + (size_t)token * N;
+        if (VEC) {
+            if (e0 < N)
+                *reinterpret_cast<float4*>(out + e0) =
+                    make_float4(g[0] * (u[0] - ubar), g[1] * (u[1] - ubar), g[2] * (u[2] - ubar), g[3] * (u[3] - ubar));
+        } else {
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                if (e0 + i < N) out[e0 + i] = g[i] * (u[i] - ubar);
+        }
+    }
+}
+
+template <int LPT>
+static void launch_gate_bwd(const float* logits, const int32_t* idx, const float* d_w, const float* penalty,
+                            const int32_t* c, float scale, int64_t S, int N, int k, float* d_logits, hipStream_t st) {
+    const dim3 grid((unsigned)ceil_div(S * LPT, kThreads)), block(kThreads);
+    const bool vec = N % 4 == 0 && reinterpret_cast<uintptr_t>(logits) % 16 == 0 &&
+                     reinterpret_cast<uintptr_t>(d_logits) % 16 == 0;
+    if (vec)
+        gate_bwd_kernel<LPT, true><<<grid, block, 0, st>>>(logits, idx, d_w, penalty, c, scale, S, N, k, d_logits);
+    else
+        gate_bwd_kernel<LPT, false><<<grid, block, 0, st>>>(logits, idx, d_w, penalty, c, scale, S, N, k, d_logits);
 }
 
 template <int DT>
@@ -244,15 +268,21 @@ extern "C" int tamoe_gate_bwd(const float* logits, const int32_t* topk_idx, cons
     const float scale =
         (float)((double)loss_scale * (penalty != nullptr ? (double)N * (double)P : 1.0) / ((double)S * (double)S));
     hipStream_t st = static_cast<hipStream_t>(stream);
-    const dim3 grid((unsigned)ceil_div(S, 128)), block(kThreads);
+    if (ceil_div(S * 32, kThreads) > 0x7fffffff) return fail(TAMOE_UNSUPPORTED, "%s: too many tokens for one launch", fn);
     {
         TraceScope tr("gate_bwd_kernel", st);
-        if (N <= 32)
-            gate_bwd_kernel<1><<<grid, block, 0, st>>>(logits, topk_idx, d_topk_w, penalty, c_expert, scale, S, N, k, d_logits);
+        if (N <= 4)
+            launch_gate_bwd<1>(logits, topk_idx, d_topk_w, penalty, c_expert, scale, S, N, k, d_logits, st);
+        else if (N <= 8)
+            launch_gate_bwd<2>(logits, topk_idx, d_topk_w, penalty, c_expert, scale, S, N, k, d_logits, st);
+        else if (N <= 16)
+            launch_gate_bwd<4>(logits, topk_idx, d_topk_w, penalty, c_expert, scale, S, N, k, d_logits, st);
+        else if (N <= 32)
+            launch_gate_bwd<8>(logits, topk_idx, d_topk_w, penalty, c_expert, scale, S, N, k, d_logits, st);
         else if (N <= 64)
-            gate_bwd_kernel<2><<<grid, block, 0, st>>>(logits, topk_idx, d_topk_w, penalty, c_expert, scale, S, N, k, d_logits);
+            launch_gate_bwd<16>(logits, topk_idx, d_topk_w, penalty, c_expert, scale, S, N, k, d_logits, st);
         else
-            gate_bwd_kernel<4><<<grid, block, 0, st>>>(logits, topk_idx, d_topk_w, penalty, c_expert, scale, S, N, k, d_logits);
+            launch_gate_bwd<32>(logits, topk_idx, d_topk_w, penalty, c_expert, scale, S, N, k, d_logits, st);
     }
     return check_launch(fn, "gate_bwd_kernel");
 }
