@@ -29,6 +29,8 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 constexpr int kKC = 64;                 // K elements per chunk (128 bytes of a bf16 row)
 constexpr int kLdsRow = kKC * 2 + 16;   // padded LDS row: 16-byte reads of 32 rows stay conflict-free
 
+constexpr int kTileRow = 36;            // floats per row of a wavefront's 32 x 32 logits tile in LDS
+
 __device__ __forceinline__ int expert_of(int nb, int v, int half) {
     return nb * 32 + ((v >> 2) << 3) + (half << 2) + (v & 3);
 }
@@ -78,16 +80,48 @@ __device__ __forceinline__ bool ranks_before(float av, int ai, float bv, int bi)
 template <int NB>
 __device__ __forceinline__ void select_tile(float (&sc)[NB][16], int lane, int64_t token, bool token_ok, int N,
                                             int k, float* __restrict__ logits, int32_t* __restrict__ topk_idx,
-                                            float* __restrict__ topk_w, float* m_wave, int32_t* hist) {
+                                            float* __restrict__ topk_w, float* m_wave, int32_t* hist,
+                                            float* tile, int64_t S) {
     const int half = lane >> 5;
-    if (logits != nullptr && token_ok) {
+    if (logits != nullptr) {
+        // The accumulator layout has one token per lane, so a direct store would write 16 bytes
+        // per lane, 512 bytes apart.  Each 32-expert block goes through a 32 x 32 tile of LDS owned
+        // by the wavefront (rows padded to 36 floats) and leaves as whole 128-byte row segments:
+        // eight lanes per row, eight rows per store instruction.
+        const int r = lane & 31;
+        const int64_t token0 = token - r;
+        const bool vec = (N & 3) == 0 && (reinterpret_cast<uintptr_t>(logits) & 15) == 0;
 #pragma unroll
-        for (int nb = 0; nb < NB; ++nb)
+        for (int nb = 0; nb < NB; ++nb) {
 #pragma unroll
-            for (int v = 0; v < 16; ++v) {
-                const int e = expert_of(nb, v, half);
-                if (e < N) logits[token * N + e] = sc[nb][v];
+            for (int q = 0; q < 4; ++q)
+                *reinterpret_cast<float4*>(&tile[r * kTileRow + 8 * q + 4 * half]) =
+                    make_float4(sc[nb][4 * q], sc[nb][4 * q + 1], sc[nb][4 * q + 2], sc[nb][4 * q + 3]);
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int rr = i * 8 + (lane >> 3);
+                const int e = nb * 32 + (lane & 7) * 4;
+                const float4 v4 = *reinterpret_cast<const float4*>(&tile[rr * kTileRow + (lane & 7) * 4]);
+                const int64_t tg = token0 + rr;
+                if (tg < S && e < N) {
+                    float* dst = logits + tg * N + e;
+                    if (vec) {
+                        // streamed: 32 MiB of dirty lines left in L2 would be written back at the
+                        // end of the kernel, after the last wavefront, with nothing to overlap
+                        typedef float f32x4 __attribute__((ext_vector_type(4)));
+                        const f32x4 o = {v4.x, v4.y, v4.z, v4.w};
+                        __builtin_nontemporal_store(o, reinterpret_cast<f32x4*>(dst));
+                    } else {
+                        dst[0] = v4.x;
+                        if (e + 1 < N) dst[1] = v4.y;
+                        if (e + 2 < N) dst[2] = v4.z;
+                        if (e + 3 < N) dst[3] = v4.w;
+                    }
+                }
             }
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+        }
     }
     if (N < NB * 32) {  // uniform
 #pragma unroll
@@ -409,7 +443,10 @@ void gate_bf16_kernel(
     for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
         for (int v = 0; v < 16; ++v) sc[nb][v] = acc[nb][v];
-    select_tile<NB>(sc, lane, token, token_ok, N, k, logits, topk_idx, topk_w, m_w[wave], hist);
+    // the K loop is over (its last stage ended with a barrier): x_lds is free, 9216 bytes per wavefront
+    float* tile = reinterpret_cast<float*>(&x_lds[0][0]) + wave * (2 * 32 * kLdsRow / 4);
+    static_assert(2 * 32 * kLdsRow >= 32 * kTileRow * 4, "logits tile must fit the wavefront's share of x_lds");
+    select_tile<NB>(sc, lane, token, token_ok, N, k, logits, topk_idx, topk_w, m_w[wave], hist, tile, S);
     store_block_partials<NB, WAVES>(m_w, hist, N, n_blocks, m_part, c_part);
 }
 
@@ -482,7 +519,7 @@ __global__ __launch_bounds__(256) void select_kernel(const float* __restrict__ l
             const int e = expert_of(nb, v, half);
             sc[nb][v] = (token_ok && e < N) ? logits[(size_t)token * N + e] : -INFINITY;
         }
-    select_tile<NB>(sc, lane, token, token_ok, N, k, nullptr, topk_idx, topk_w, m_w[wave], hist);
+    select_tile<NB>(sc, lane, token, token_ok, N, k, nullptr, topk_idx, topk_w, m_w[wave], hist, nullptr, S);
     store_block_partials<NB, 4>(m_w, hist, N, n_blocks, m_part, c_part);
 }
 
