@@ -279,6 +279,40 @@ def main():
                              "achieved_GBs": round(gbs, 1), "frac_of_hbm_peak": round(gbs / HBM_PEAK_GBS, 4)})
         del logits, d_recv, d_w, d_logits, d_x
 
+    # Receive-side regrouping (next row of the scope): the K_now rows of `send` stand in for a receive
+    # buffer with P source chunks x E local experts (E = 2 when the workload has one expert per device,
+    # where regrouping is the identity), seeded Poisson segment sizes.  Untimed pass, not part of `value`.
+    regroup = None
+    if not args.no_backward:
+        E_r = wl.E if wl.E > 1 else 2
+        P_r = min(wl.P, 128 // E_r)
+        rows_r = int(off[-1].item())
+        if rows_r >= P_r * E_r:
+            rng = np.random.Generator(np.random.Philox(key=[wl.seed, 11]))
+            share = rng.poisson(64, size=(P_r, E_r)).astype(np.float64) + 1.0
+            cnt = np.floor(share / share.sum() * rows_r).astype(np.int32)
+            cnt[0, 0] += rows_r - int(cnt.sum())
+            cnt_d = torch.from_numpy(cnt).to(dev)
+            rin = send[:rows_r]
+            rout = torch.empty_like(rin)
+            for _ in range(2):
+                T.tamoe_regroup(rin, cnt_d, True, rout, None, ws, None)
+            torch.cuda.synchronize()
+            T.tamoe_trace_filter("regroup_copy_kernel")
+            T.tamoe_trace_start(10)
+            for _ in range(10):
+                T.tamoe_regroup(rin, cnt_d, True, rout, None, ws, None)
+            torch.cuda.synchronize()
+            rec = collect()
+            T.tamoe_trace_filter(None)
+            T.tamoe_trace_clear()
+            us = float(np.mean(rec["regroup_copy_kernel"])) * 1e3
+            rb = 2 * rows_r * d * b
+            regroup = {"kernel": "regroup_copy_kernel", "P": P_r, "E": E_r, "rows": rows_r, "avg_us": round(us, 2),
+                       "algo_bytes": int(rb), "achieved_GBs": round(rb / (us * 1e-6) / 1e9, 1),
+                       "frac_of_hbm_peak": round(rb / (us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)}
+            del rout
+
     ms_per_step = elapsed * 1e3 / args.steps
     tokens_per_s = S * args.steps / elapsed
 
@@ -343,6 +377,7 @@ def main():
         "mix_probe": mix,
         "kernels": kernels,
         "backward_kernels": backward,
+        "regroup_kernel": regroup,
         "l_topo": float(loss.item()),
         "mode": "graph replay" if args.graph else "eager",
         "kernels_table_from": f"untimed pass of {table_steps} steps with HIP events around every launch",

@@ -205,6 +205,25 @@ int tamoe_dispatch_bwd(const void* d_send, int64_t K_rows, const int32_t* slot, 
                        int64_t S, int d, int k, void* d_x, void* stream);
 
 /*
+ * Receive side: regroup the rows of the global exchange per local expert (Section 3.1: each
+ * expert receives a combined batch of tokens; rows from process s for expert e: c_se).
+ * The receive buffer `in` holds one chunk per source device s = 0..P-1, in that order; inside a
+ * chunk the rows are grouped by local expert e = 0..E-1, recv_count[s*E + e] rows each
+ * (source-major).  Expert-major lists, for e = 0..E-1, the segments of s = 0..P-1 in that order,
+ * so that every local expert has one contiguous batch.
+ *   to_expert_major != 0: in is source-major, out becomes expert-major (before the experts);
+ *   to_expert_major == 0: the inverse (before the return exchange).
+ * expert_offset [E+1] (may be NULL): first row of every expert's batch, expert_offset[E] = rows.
+ * cap_rows = number of rows both buffers can hold; only the first R = sum of the counts rows are
+ * read and written (R is taken on the device; rows beyond cap_rows are dropped).  P*E <= 128.
+ * in, out [cap_rows, d] `dtype`, recv_count [P*E], expert_offset: device.  ws: at least
+ * tamoe_workspace_bytes(...) (any shape) bytes.
+ */
+int tamoe_regroup(const void* in, const int32_t* recv_count, int P, int E, int dtype, int d,
+                  int64_t cap_rows, int to_expert_major, void* out, int32_t* expert_offset,
+                  void* ws, size_t ws_bytes, void* stream);
+
+/*
  * Kernel timing aid for benchmarks (not a step of the path; off unless started).
  * tamoe_trace_start creates 2*max_launches HIP events on the current device; from then on every
  * kernel the device functions above enqueue is bracketed by a pair of events on its stream,

@@ -62,6 +62,7 @@ def _load():
         "orc_gate_bwd": (None, [c_vp, c_vp, c_vp, c_vp, c_vp, c_dbl, c_i64, c_i32, c_i32, c_i32, c_vp]),
         "orc_combine_bwd": (None, [c_vp, c_vp, c_i32, c_vp, c_vp, c_i64, c_i64, c_i32, c_i32, c_vp, c_vp, c_vp]),
         "orc_dispatch_bwd": (None, [c_vp, c_i32, c_vp, c_i64, c_i32, c_i32, c_vp, c_vp]),
+        "orc_regroup": (c_i64, [c_vp, c_i32, c_vp, c_i32, c_i32, c_i32, c_i32, c_vp, c_vp]),
     }
     for name, (res, args) in sig.items():
         fn = getattr(lib, name)
@@ -282,6 +283,22 @@ def dispatch_bwd(dsend, dtype: int, slot, want_rounded: bool = True):
     dx = np.empty((S, d), dtype=dsend.dtype) if want_rounded else None
     _load().orc_dispatch_bwd(_p(dsend), dtype, _p(slot), S, d, k, _p(dx_exact), _p(dx))
     return dx_exact, dx
+
+
+# ---- receive side ---------------------------------------------------------------
+
+def regroup(rows_in, dtype: int, cnt, to_expert_major: bool):
+    """cnt [P,E]: rows from source s for local expert e.  Returns (rows_out, expert_offset[E+1])."""
+    rows_in = _storage(rows_in, dtype)
+    cnt = _c(cnt, np.int32)
+    P, E = cnt.shape
+    R, d = rows_in.shape
+    assert int(cnt.sum()) == R
+    out = np.zeros_like(rows_in)
+    eoff = np.empty((E + 1,), dtype=np.int32)
+    got = _load().orc_regroup(_p(rows_in), dtype, _p(cnt), P, E, d, 1 if to_expert_major else 0, _p(out), _p(eoff))
+    assert got == R
+    return out, eoff
 
 
 # ---- whole path (the steps above, in the paper's order) -----------------------

@@ -508,3 +508,49 @@ void orc_dispatch_bwd(const void *dsend, int dtype, const int32_t *slot, int64_t
         }
     }
 }
+
+/* ---- receive side: rows of the exchange regrouped per local expert --------------------------- */
+
+/*
+ * After the global exchange (Section 3.1: each expert receives a combined batch of tokens) this
+ * device holds one chunk per source device s = 0..P-1, in that order; inside a chunk the rows are
+ * grouped by local expert e = 0..E-1 (the sender's buffer lists rows expert by expert), cnt[s][e]
+ * rows each (the c_se of Section 3.1 after capacity).  The experts need one batch each:
+ *   expert-major layout = for e = 0..E-1, for s = 0..P-1: the cnt[s][e] rows of (s, e).
+ * to_expert_major != 0 converts source-major -> expert-major, 0 converts back (for the return
+ * exchange).  expert_offset[e] (E+1 entries, may be NULL) = first row of expert e's batch.
+ * Returns the number of rows R.
+ */
+int64_t orc_regroup(const void *in, int dtype, const int32_t *cnt, int P, int E, int d,
+                    int to_expert_major, void *out, int32_t *expert_offset)
+{
+    size_t row = (size_t)d * elem_size(dtype);
+    int64_t src_pos = 0; /* position in the source-major buffer */
+    for (int s = 0; s < P; ++s) {
+        for (int e = 0; e < E; ++e) {
+            /* position of segment (s, e) in the expert-major buffer */
+            int64_t em_pos = 0;
+            for (int ee = 0; ee < E; ++ee)
+                for (int ss = 0; ss < P; ++ss)
+                    if (ee < e || (ee == e && ss < s))
+                        em_pos += cnt[ss * E + ee];
+            for (int32_t r = 0; r < cnt[s * E + e]; ++r) {
+                if (to_expert_major)
+                    memcpy((char *)out + (size_t)(em_pos + r) * row, (const char *)in + (size_t)(src_pos + r) * row, row);
+                else
+                    memcpy((char *)out + (size_t)(src_pos + r) * row, (const char *)in + (size_t)(em_pos + r) * row, row);
+            }
+            src_pos += cnt[s * E + e];
+        }
+    }
+    if (expert_offset) {
+        int64_t acc = 0;
+        for (int e = 0; e < E; ++e) {
+            expert_offset[e] = (int32_t)acc;
+            for (int s = 0; s < P; ++s)
+                acc += cnt[s * E + e];
+        }
+        expert_offset[E] = (int32_t)acc;
+    }
+    return src_pos;
+}

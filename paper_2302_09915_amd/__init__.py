@@ -32,7 +32,7 @@ OK, INVALID_ARG, UNSUPPORTED, WORKSPACE_TOO_SMALL, HIP_ERROR = 0, 1, 2, 3, 4
 EXPORTS = (
     "tamoe_version", "tamoe_last_error", "tamoe_topo_pattern", "tamoe_workspace_bytes",
     "tamoe_gate", "tamoe_select", "tamoe_aux_loss", "tamoe_dispatch", "tamoe_combine",
-    "tamoe_gate_bwd", "tamoe_combine_bwd", "tamoe_dispatch_bwd",
+    "tamoe_gate_bwd", "tamoe_combine_bwd", "tamoe_dispatch_bwd", "tamoe_regroup",
     "tamoe_trace_start", "tamoe_trace_filter", "tamoe_trace_stop", "tamoe_trace_get", "tamoe_trace_clear", "tamoe_copy_probe", "tamoe_mix_probe",
 )
 
@@ -80,6 +80,8 @@ def lib() -> ctypes.CDLL:
     L.tamoe_combine_bwd.argtypes = [vp, vp, i64, vp, vp, i32, i64, i32, i32, vp, vp, vp]
     L.tamoe_dispatch_bwd.restype = i32
     L.tamoe_dispatch_bwd.argtypes = [vp, i64, vp, i32, i64, i32, i32, vp, vp]
+    L.tamoe_regroup.restype = i32
+    L.tamoe_regroup.argtypes = [vp, vp, i32, i32, i32, i32, i64, i32, vp, vp, vp, sz, vp]
     L.tamoe_trace_start.restype = i32
     L.tamoe_trace_start.argtypes = [i32]
     L.tamoe_trace_filter.restype = i32
@@ -258,6 +260,19 @@ def tamoe_dispatch_bwd(d_send, K_rows: int, slot, d_x, stream=None) -> None:
     _check(lib().tamoe_dispatch_bwd(
         _dev(d_send, None, "d_send"), K_rows, _dev(slot, torch.int32, "slot"), _dtype_code(d_x), S, d, k,
         _dev(d_x, None, "d_x"), _stream(stream)))
+
+
+def tamoe_regroup(rows_in, recv_count, to_expert_major: bool, rows_out, expert_offset, ws, stream=None) -> None:
+    """recv_count [P,E] int32 (device); rows_in / rows_out [cap_rows, d]."""
+    P, E = recv_count.shape
+    cap_rows, d = rows_in.shape
+    if rows_out.shape != rows_in.shape or rows_out.dtype != rows_in.dtype:
+        raise TamoeError(INVALID_ARG, "rows_out must have the shape and dtype of rows_in")
+    wsp, wsn = _ws(ws)
+    _check(lib().tamoe_regroup(
+        _dev(rows_in, None, "rows_in"), _dev(recv_count, torch.int32, "recv_count"), P, E, _dtype_code(rows_in), d,
+        cap_rows, 1 if to_expert_major else 0, _dev(rows_out, None, "rows_out"),
+        _dev(expert_offset, torch.int32, "expert_offset"), wsp, wsn, _stream(stream)))
 
 
 def tamoe_trace_start(max_launches: int) -> None:

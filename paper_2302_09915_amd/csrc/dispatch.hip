@@ -18,6 +18,7 @@
 // bytes per kept pair.  Chunks are laid out flat over the threads, so a wavefront always touches
 // 1 KiB of consecutive bytes, whatever d is.
 #include "internal.h"
+#include "scan128.h"
 
 namespace tamoe {
 
@@ -60,29 +61,6 @@ __global__ __launch_bounds__(kThreads) void dispatch_count_kernel(
         const int j = q / N, e = q - j * N;
         tile_count[((size_t)j * n_ct + ct) * N + e] = hist[q];
     }
-}
-
-// Exclusive prefix sum of v[0..n) (n <= 128) into out[0..n], out[n] = total.  Called by every
-// thread of the workgroup (at least 128 threads); tmp is 256 ints of LDS; v, out, tmp in LDS.
-__device__ __forceinline__ void exclusive_scan_128(const int32_t* v, int32_t* out, int32_t* tmp, int n) {
-    const int t = threadIdx.x;
-    const int32_t mine = (t < n) ? v[t] : 0;
-    if (t < 128) tmp[t] = mine;
-    __syncthreads();
-    int cur = 0;
-#pragma unroll
-    for (int s = 1; s < 128; s <<= 1) {
-        if (t < 128) tmp[(cur ^ 1) * 128 + t] = tmp[cur * 128 + t] + (t >= s ? tmp[cur * 128 + t - s] : 0);
-        __syncthreads();
-        cur ^= 1;
-    }
-    if (t < n) {
-        const int32_t incl = tmp[cur * 128 + t];
-        out[t] = incl - mine;
-        if (t == n - 1) out[n] = incl;
-    }
-    if (n == 0 && t == 0) out[0] = 0;
-    __syncthreads();
 }
 
 // kept rows per expert -> the three size outputs of tamoe_dispatch (kept and off in LDS)
