@@ -46,6 +46,9 @@ def parse_args():
                     help="no HIP events inside the timed region (per-kernel times then come from an extra traced pass)")
     ap.add_argument("--graph", action="store_true",
                     help="capture one step in a HIP graph and time replays (implies --no-trace)")
+    ap.add_argument("--rotate", type=int, default=1,
+                    help="number of copies of (x, send, y) that the steps cycle through, so that a small workload's "
+                         "rows come from HBM and not from the 256 MB last-level cache (default 1: same buffers)")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target CPU time of the oracle sample")
     return ap.parse_args()
 
@@ -145,14 +148,19 @@ def main():
     scd = torch.empty((P,), dtype=i32, device=dev)
     y = torch.empty((S, d), dtype=x.dtype, device=dev)
     stream = torch.cuda.current_stream()
+    rotate = max(1, args.rotate)
+    sets = [(x, send, y)] + [(x.clone(), torch.empty_like(send), torch.empty_like(y)) for _ in range(rotate - 1)]
+    turn = [0]
 
     def step():
+        xs, sends, ys = sets[turn[0] % rotate]
+        turn[0] += 1
         # stream=None: the binding passes torch's current stream (the capture stream under --graph)
-        T.tamoe_gate(x, w, P, k, None, topk_idx, topk_w, m, c_expert, c_device, ws, None)
+        T.tamoe_gate(xs, w, P, k, None, topk_idx, topk_w, m, c_expert, c_device, ws, None)
         T.tamoe_aux_loss(m, c_expert, pen_d, P, S, loss, None)
-        T.tamoe_dispatch(x, topk_idx, cap_d, N, P, send, slot, kept, off, scd, ws, None)
+        T.tamoe_dispatch(xs, topk_idx, cap_d, N, P, sends, slot, kept, off, scd, ws, None)
         # identity expert: the rows come back as they were sent; S*k bounds the row count
-        T.tamoe_combine(send, S * k, slot, topk_w, y, None)
+        T.tamoe_combine(sends, S * k, slot, topk_w, ys, None)
 
     for _ in range(max(args.warmup, 0)):
         step()
@@ -216,7 +224,7 @@ def main():
         # the library only enqueues kernels on the current stream, so a step can be captured as is
         graph = torch.cuda.CUDAGraph()
         with torch.cuda.graph(graph):
-            step()
+            step()                               # with --rotate the replays reuse the captured set
         run_step = graph.replay
         for _ in range(2):
             run_step()
@@ -368,7 +376,7 @@ def main():
                    "capacity_factor": wl.capacity_factor, "cap_mode": args.cap_mode,
                    "topology": f"{wl.nodes}x{wl.devs_per_node} ratio {wl.bw_ratio:g}:1", "rank": wl.rank,
                    "kept_rows_K": K, "tokens_with_a_kept_choice": live_tokens,
-                   "drop_rate": round(1.0 - K / (S * k), 4)},
+                   "drop_rate": round(1.0 - K / (S * k), 4), "rotating_buffer_sets": rotate},
         "path_algo_bytes_per_step": int(total_algo),
         "path_achieved_GBs": round(total_algo / (ms_per_step * 1e-3) / 1e9, 1),
         "roofline": roofline,

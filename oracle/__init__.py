@@ -62,6 +62,10 @@ def _load():
         "orc_gate_bwd": (None, [c_vp, c_vp, c_vp, c_vp, c_vp, c_dbl, c_i64, c_i32, c_i32, c_i32, c_vp]),
         "orc_combine_bwd": (None, [c_vp, c_vp, c_i32, c_vp, c_vp, c_i64, c_i64, c_i32, c_i32, c_vp, c_vp, c_vp]),
         "orc_dispatch_bwd": (None, [c_vp, c_i32, c_vp, c_i64, c_i32, c_i32, c_vp, c_vp]),
+        "orc_penalty_softmax": (None, [c_vp, c_i32, c_dbl, c_vp]),
+        "orc_renorm_topk": (None, [c_vp, c_i64, c_i32, c_vp]),
+        "orc_renorm_topk_bwd": (None, [c_vp, c_vp, c_i64, c_i32, c_vp]),
+        "orc_slots_padded": (None, [c_vp, c_vp, c_i64, c_i32, c_i32, c_i32, c_vp, c_vp]),
         "orc_regroup": (c_i64, [c_vp, c_i32, c_vp, c_i32, c_i32, c_i32, c_i32, c_vp, c_vp]),
     }
     for name, (res, args) in sig.items():
@@ -127,6 +131,13 @@ def penalty(c_hat) -> np.ndarray:
     c_hat = _c(c_hat, np.float64)
     out = np.empty_like(c_hat)
     _load().orc_penalty(_p(c_hat), c_hat.shape[0], _p(out))
+    return out
+
+
+def penalty_softmax(c_hat, tau: float) -> np.ndarray:
+    c_hat = _c(c_hat, np.float64)
+    out = np.empty_like(c_hat)
+    _load().orc_penalty_softmax(_p(c_hat), c_hat.shape[0], float(tau), _p(out))
     return out
 
 
@@ -219,6 +230,34 @@ def slots(idx, cap, P: int):
     scd = np.empty((P,), dtype=np.int32)
     K = _load().orc_slots(_p(idx), _p(cap), S, N, P, k, _p(slot), _p(kept), _p(off), _p(scd))
     return slot, kept, off, scd, int(K)
+
+
+def slots_padded(idx, cap, N: int, C: int):
+    """Fixed-size layout: slot = e*C + pos (or -1), kept[e].  cap may be None."""
+    idx = _c(idx, np.int32)
+    S, k = idx.shape
+    cap = None if cap is None else _c(cap, np.int32)
+    slot = np.empty((S, k), dtype=np.int32)
+    kept = np.empty((N,), dtype=np.int32)
+    _load().orc_slots_padded(_p(idx), _p(cap), S, N, k, C, _p(slot), _p(kept))
+    return slot, kept
+
+
+def renorm_topk(wgt) -> np.ndarray:
+    wgt = _c(wgt, np.float64)
+    S, k = wgt.shape
+    out = np.empty_like(wgt)
+    _load().orc_renorm_topk(_p(wgt), S, k, _p(out))
+    return out
+
+
+def renorm_topk_bwd(wgt, d_out) -> np.ndarray:
+    wgt = _c(wgt, np.float64)
+    d_out = _c(d_out, np.float64)
+    S, k = wgt.shape
+    out = np.empty_like(wgt)
+    _load().orc_renorm_topk_bwd(_p(wgt), _p(d_out), S, k, _p(out))
+    return out
 
 
 def scatter(x, dtype: int, slot, K: int) -> np.ndarray:

@@ -22,8 +22,8 @@
  * Every function below is pinned by tests/test_oracle_*.py against closed
  * forms, invariants, brute force, library routines and the worked numbers of
  * the paper's Table 1.  Not pinned ("parity unpinned"): none of the exported
- * functions; the paper's softmax-type Norm, asymmetric-tree merge and global
- * capacity are not implemented here at all.
+ * functions; the paper's asymmetric-tree merge and global capacity are not
+ * implemented here at all.
  */
 #include <math.h>
 #include <stdint.h>
@@ -179,6 +179,35 @@ void orc_penalty(const double *c_hat, int N, double *p)
 }
 
 /*
+ * Softmax-type Norm of the penalty (Section 4.3, the sentence after the penalty
+ * equation: normalisations that enlarge the penalty of slow transfers, such as
+ * softmax, are admissible too).  The paper gives no scale for the softmax
+ * argument; here it is explicit: r[e] = (1/c_hat[e]) / mean_e'(1/c_hat[e'])
+ * (the inverse pattern in units of its mean), p[e] = exp(tau*r[e]) / sum_e'
+ * exp(tau*r[e']).  tau = 0 gives the uniform weight 1/N.
+ */
+void orc_penalty_softmax(const double *c_hat, int N, double tau, double *p)
+{
+    double tot = 0.0;
+    for (int e = 0; e < N; ++e)
+        tot += 1.0 / c_hat[e];
+    double mean = tot / (double)N;
+    double zmax = -INFINITY;
+    for (int e = 0; e < N; ++e) {
+        p[e] = tau * ((1.0 / c_hat[e]) / mean);
+        if (p[e] > zmax)
+            zmax = p[e];
+    }
+    double den = 0.0;
+    for (int e = 0; e < N; ++e) {
+        p[e] = exp(p[e] - zmax);
+        den += p[e];
+    }
+    for (int e = 0; e < N; ++e)
+        p[e] /= den;
+}
+
+/*
  * Local capacity per expert (Section 3.1, last paragraph, and Section 4.3,
  * the paragraph on DeepSpeed-MoE): mode 0 is the uniform capacity at the
  * load-balanced target, ceil(cf * k*S/N); mode 1 makes it proportional to
@@ -324,6 +353,37 @@ double orc_l_topo(const double *p, const double *m, const int32_t *c, int N, int
     return (double)N * (double)P * l;
 }
 
+/*
+ * Combine weights renormalised over a token's k selected experts (a variant of the weighting
+ * G(x)_e of Section 3.1 in which the k weights of a token sum to one):
+ *   out[t][j] = wgt[t][j] / sum_j' wgt[t][j'].
+ */
+void orc_renorm_topk(const double *wgt, int64_t S, int k, double *out)
+{
+    for (int64_t t = 0; t < S; ++t) {
+        double s = 0.0;
+        for (int j = 0; j < k; ++j)
+            s += wgt[t * k + j];
+        for (int j = 0; j < k; ++j)
+            out[t * k + j] = wgt[t * k + j] / s;
+    }
+}
+
+/* Its transpose for a gradient d_out that arrives at the renormalised weights:
+ *   d_wgt[t][i] = d_out[t][i] / s - (sum_j d_out[t][j] * wgt[t][j]) / s^2,  s = sum_j wgt[t][j]. */
+void orc_renorm_topk_bwd(const double *wgt, const double *d_out, int64_t S, int k, double *d_wgt)
+{
+    for (int64_t t = 0; t < S; ++t) {
+        double s = 0.0, dot = 0.0;
+        for (int j = 0; j < k; ++j) {
+            s += wgt[t * k + j];
+            dot += d_out[t * k + j] * wgt[t * k + j];
+        }
+        for (int i = 0; i < k; ++i)
+            d_wgt[t * k + i] = d_out[t * k + i] / s - dot / (s * s);
+    }
+}
+
 /* ---- capacity-limited dispatch and combine ------------------------------- */
 
 /*
@@ -368,6 +428,32 @@ int64_t orc_slots(const int32_t *idx, const int32_t *cap, int64_t S, int N, int 
     free(counter);
     free(pos);
     return (int64_t)off[N];
+}
+
+/*
+ * Fixed-size zero-padded layout (Section 4.3, last paragraph: the layout of DeepSpeed-MoE that
+ * the variable chunk sizes replace; Section 3.1: local capacity).  Every expert owns C rows of
+ * the buffer whether it fills them or not: slot = e*C + pos for a pair with pos < min(cap[e], C)
+ * (cap may be NULL: the limit is C alone), -1 otherwise; kept[e] = min(c[e], cap[e], C).  Rows
+ * e*C + kept[e] .. (e+1)*C - 1 stay zero.  The pair order is that of orc_slots.
+ */
+void orc_slots_padded(const int32_t *idx, const int32_t *cap, int64_t S, int N, int k, int C,
+                      int32_t *slot, int32_t *kept)
+{
+    int32_t *counter = (int32_t *)calloc((size_t)N, sizeof(int32_t));
+    for (int j = 0; j < k; ++j) {
+        for (int64_t t = 0; t < S; ++t) {
+            int e = idx[t * k + j];
+            int32_t lim = cap != NULL && cap[e] < C ? cap[e] : C;
+            slot[t * k + j] = counter[e] < lim ? e * C + counter[e] : -1;
+            counter[e] += 1;
+        }
+    }
+    for (int e = 0; e < N; ++e) {
+        int32_t lim = cap != NULL && cap[e] < C ? cap[e] : C;
+        kept[e] = counter[e] < lim ? counter[e] : lim;
+    }
+    free(counter);
 }
 
 /* Scatter (Section 3.1: dispatched data of shape [k*S, d], [c_ie, d] per expert): a bit copy
