@@ -63,6 +63,7 @@ typedef enum tamoe_status {
 
 enum { TAMOE_F32 = 0, TAMOE_BF16 = 1 };
 enum { TAMOE_CAP_UNIFORM = 0, TAMOE_CAP_PROPORTIONAL = 1 };
+enum { TAMOE_NORM_L1 = 0, TAMOE_NORM_SOFTMAX = 1 };
 
 int tamoe_version(void);
 
@@ -91,6 +92,20 @@ const char* tamoe_last_error(void);
 int tamoe_topo_pattern(const double* beta, const int32_t* level, int P, int N, int rank, int k,
                        int64_t S, double capacity_factor, int cap_mode,
                        double* c_hat, float* penalty, int32_t* cap);
+
+/*
+ * Penalty from a target pattern with a chosen Norm, host only (Section 4.3: p_i = Norm(1/c_hat_i);
+ * besides the plain normalisation, functions that enlarge the penalty of slow transfers, softmax
+ * for one, are admissible).
+ *   TAMOE_NORM_L1:       penalty[e] = (1/c_hat[e]) / sum_e' (1/c_hat[e'])   (what tamoe_topo_pattern returns)
+ *   TAMOE_NORM_SOFTMAX:  r[e] = (1/c_hat[e]) / mean_e' (1/c_hat[e']),
+ *                        penalty[e] = exp(temperature * r[e]) / sum_e' exp(temperature * r[e'])
+ * The paper leaves the scale of the softmax argument open; it is the explicit `temperature` here
+ * (>= 0; 0 gives 1/N; ignored for TAMOE_NORM_L1).  On a two-tier pattern with bandwidth ratio rho
+ * the slow/fast penalty ratio exceeds the L1 ratio rho once temperature > ln(rho) / (r_slow - r_fast).
+ * c_hat [N] double (> 0, finite), penalty [N] float: host.
+ */
+int tamoe_penalty(const double* c_hat, int N, int norm, double temperature, float* penalty);
 
 /* Bytes of device workspace that any of the device functions below needs for this shape. */
 size_t tamoe_workspace_bytes(int64_t S, int d, int N, int P, int k, int dtype);
@@ -203,6 +218,35 @@ int tamoe_combine_bwd(const void* dy, const void* recv, int64_t K_rows, const in
  */
 int tamoe_dispatch_bwd(const void* d_send, int64_t K_rows, const int32_t* slot, int dtype,
                        int64_t S, int d, int k, void* d_x, void* stream);
+
+/*
+ * Combine weights renormalised over the k selected experts of a token (a variant of the weighting
+ * G(x)_e of Section 3.1 in which a token's k weights sum to one; taken before any capacity drop):
+ *   out[t][j] = topk_w[t][j] / (topk_w[t][0] + ... + topk_w[t][k-1])      fp32, sum in ascending j
+ * and its transpose for a gradient d_out [S,k] that arrives at the renormalised weights:
+ *   d_topk_w[t][i] = d_out[t][i] / s - (sum_j d_out[t][j] * topk_w[t][j]) / s^2,   s = sum_j topk_w[t][j]
+ * (feed d_topk_w to tamoe_gate_bwd).  All pointers device, [S,k] float; out may alias topk_w and
+ * d_topk_w may alias d_out.
+ */
+int tamoe_renorm_topk(const float* topk_w, int64_t S, int k, float* out, void* stream);
+int tamoe_renorm_topk_bwd(const float* topk_w, const float* d_out, int64_t S, int k, float* d_topk_w,
+                          void* stream);
+
+/*
+ * Dispatch into the fixed-size zero-padded layout that the variable chunk sizes of Section 4.3
+ * replace: every expert owns C rows of `send` whether it fills them or not (so every destination
+ * device receives E*C rows).  Same pair order as tamoe_dispatch; a pair is kept iff
+ * pos < min(cap[e], C) (cap == NULL: pos < C).
+ *   kept_expert[e]  = min(c_expert[e], cap[e], C)
+ *   slot[t][j]      = e*C + pos  if kept, else -1
+ *   send[slot[t][j]][:] = x[t][:];  rows e*C + kept_expert[e] .. (e+1)*C - 1 are set to zero
+ * tamoe_combine works on this layout unchanged (K_rows = N*C).
+ * send: device, [N*C, d] `dtype`, every row written; N*C < 2^31.  Other arguments as tamoe_dispatch.
+ */
+int tamoe_dispatch_padded(const void* x, const int32_t* topk_idx, const int32_t* cap, int dtype,
+                          int64_t S, int d, int N, int P, int k, int C,
+                          void* send, int32_t* slot, int32_t* kept_expert,
+                          void* ws, size_t ws_bytes, void* stream);
 
 /*
  * Receive side: regroup the rows of the global exchange per local expert (Section 3.1: each

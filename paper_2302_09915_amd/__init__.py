@@ -24,6 +24,8 @@ F32 = 0
 BF16 = 1
 CAP_UNIFORM = 0
 CAP_PROPORTIONAL = 1
+NORM_L1 = 0
+NORM_SOFTMAX = 1
 MAX_EXPERTS = 128
 MAX_K = 8
 
@@ -33,6 +35,7 @@ EXPORTS = (
     "tamoe_version", "tamoe_last_error", "tamoe_topo_pattern", "tamoe_workspace_bytes",
     "tamoe_gate", "tamoe_select", "tamoe_aux_loss", "tamoe_dispatch", "tamoe_combine",
     "tamoe_gate_bwd", "tamoe_combine_bwd", "tamoe_dispatch_bwd", "tamoe_regroup",
+    "tamoe_penalty", "tamoe_renorm_topk", "tamoe_renorm_topk_bwd", "tamoe_dispatch_padded",
     "tamoe_trace_start", "tamoe_trace_filter", "tamoe_trace_stop", "tamoe_trace_get", "tamoe_trace_clear", "tamoe_copy_probe", "tamoe_mix_probe",
 )
 
@@ -82,6 +85,14 @@ def lib() -> ctypes.CDLL:
     L.tamoe_dispatch_bwd.argtypes = [vp, i64, vp, i32, i64, i32, i32, vp, vp]
     L.tamoe_regroup.restype = i32
     L.tamoe_regroup.argtypes = [vp, vp, i32, i32, i32, i32, i64, i32, vp, vp, vp, sz, vp]
+    L.tamoe_penalty.restype = i32
+    L.tamoe_penalty.argtypes = [vp, i32, i32, dbl, vp]
+    L.tamoe_renorm_topk.restype = i32
+    L.tamoe_renorm_topk.argtypes = [vp, i64, i32, vp, vp]
+    L.tamoe_renorm_topk_bwd.restype = i32
+    L.tamoe_renorm_topk_bwd.argtypes = [vp, vp, i64, i32, vp, vp]
+    L.tamoe_dispatch_padded.restype = i32
+    L.tamoe_dispatch_padded.argtypes = [vp, vp, vp, i32, i64, i32, i32, i32, i32, i32, vp, vp, vp, vp, sz, vp]
     L.tamoe_trace_start.restype = i32
     L.tamoe_trace_start.argtypes = [i32]
     L.tamoe_trace_filter.restype = i32
@@ -169,6 +180,15 @@ def tamoe_topo_pattern(beta, level, P: int, N: int, rank: int, k: int, S: int, c
     return c_hat, pen, cap
 
 
+def tamoe_penalty(c_hat, norm: int, temperature: float = 1.0) -> np.ndarray:
+    """Host.  c_hat f64[N] -> penalty f32[N] with Norm `norm` (NORM_L1 / NORM_SOFTMAX)."""
+    c_hat = np.ascontiguousarray(c_hat, dtype=np.float64)
+    pen = np.empty(c_hat.shape[0], dtype=np.float32)
+    _check(lib().tamoe_penalty(c_hat.ctypes.data_as(ctypes.c_void_p), c_hat.shape[0], norm, float(temperature),
+                               pen.ctypes.data_as(ctypes.c_void_p)))
+    return pen
+
+
 def tamoe_workspace_bytes(S: int, d: int, N: int, P: int, k: int, dtype: int) -> int:
     return int(lib().tamoe_workspace_bytes(S, d, N, P, k, dtype))
 
@@ -216,6 +236,35 @@ def tamoe_dispatch(x, topk_idx, cap, N: int, P: int, send, slot, kept_expert, ex
         _dtype_code(x), S, d, N, P, k, _dev(send, None, "send"), _dev(slot, torch.int32, "slot"),
         _dev(kept_expert, torch.int32, "kept_expert"), _dev(expert_offset, torch.int32, "expert_offset"),
         _dev(send_count_dev, torch.int32, "send_count_dev"), wsp, wsn, _stream(stream)))
+
+
+def tamoe_dispatch_padded(x, topk_idx, cap, N: int, P: int, C: int, send, slot, kept_expert, ws, stream=None) -> None:
+    """send [N*C, d]; cap may be None (the limit is C alone)."""
+    S, d = x.shape
+    k = topk_idx.shape[1]
+    wsp, wsn = _ws(ws)
+    if send is None or send.dtype != x.dtype or send.numel() != N * C * d:
+        raise TamoeError(INVALID_ARG, "send must have the dtype of x and exactly N*C rows")
+    _check(lib().tamoe_dispatch_padded(
+        _dev(x, None, "x"), _dev(topk_idx, torch.int32, "topk_idx"), _dev(cap, torch.int32, "cap"),
+        _dtype_code(x), S, d, N, P, k, C, _dev(send, None, "send"), _dev(slot, torch.int32, "slot"),
+        _dev(kept_expert, torch.int32, "kept_expert"), wsp, wsn, _stream(stream)))
+
+
+def tamoe_renorm_topk(topk_w, out, stream=None) -> None:
+    S, k = topk_w.shape
+    if out is None or out.shape != topk_w.shape:
+        raise TamoeError(INVALID_ARG, "out must have the shape of topk_w")
+    _check(lib().tamoe_renorm_topk(_dev(topk_w, torch.float32, "topk_w"), S, k, _dev(out, torch.float32, "out"),
+                                   _stream(stream)))
+
+
+def tamoe_renorm_topk_bwd(topk_w, d_out, d_topk_w, stream=None) -> None:
+    S, k = topk_w.shape
+    if d_out is None or d_topk_w is None or d_out.shape != topk_w.shape or d_topk_w.shape != topk_w.shape:
+        raise TamoeError(INVALID_ARG, "d_out and d_topk_w must have the shape of topk_w")
+    _check(lib().tamoe_renorm_topk_bwd(_dev(topk_w, torch.float32, "topk_w"), _dev(d_out, torch.float32, "d_out"),
+                                       S, k, _dev(d_topk_w, torch.float32, "d_topk_w"), _stream(stream)))
 
 
 def tamoe_combine(recv, K_rows: int, slot, topk_w, y, stream=None) -> None:

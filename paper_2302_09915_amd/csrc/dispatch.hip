@@ -69,11 +69,19 @@ __device__ __forceinline__ void write_sizes(const int32_t* kept, const int32_t* 
                                             int32_t* __restrict__ send_count_dev) {
     const int t = threadIdx.x;
     if (t < N) kept_expert[t] = kept[t];
-    if (t <= N) expert_offset[t] = off[t];
-    if (t < P) {
+    if (expert_offset != nullptr && t <= N) expert_offset[t] = off[t];
+    if (send_count_dev != nullptr && t < P) {
         const int E = N / P;
         send_count_dev[t] = off[(t + 1) * E] - off[t * E];
     }
+}
+
+// Pairs of expert e that may be kept: its capacity (none given: unlimited), and in the fixed-size
+// layout (pad_C > 0) at most the pad_C rows that every expert owns.
+__device__ __forceinline__ int32_t pair_limit(const int32_t* __restrict__ cap, int e, int pad_C) {
+    int32_t c = cap != nullptr ? (cap[e] < 0 ? 0 : cap[e]) : 0x7fffffff;
+    if (pad_C > 0 && c > pad_C) c = pad_C;
+    return c;
 }
 
 // One workgroup of 1024 threads: thread (part, e) owns a contiguous eighth of expert e's
@@ -82,7 +90,7 @@ constexpr int kScanThreads = 1024;
 constexpr int kScanParts = kScanThreads / TAMOE_MAX_EXPERTS;
 
 __global__ __launch_bounds__(kScanThreads) void dispatch_scan_kernel(
-    int32_t* __restrict__ tile_count, const int32_t* __restrict__ cap, int N, int P, int n_entries,
+    int32_t* __restrict__ tile_count, const int32_t* __restrict__ cap, int N, int P, int n_entries, int pad_C,
     int32_t* __restrict__ kept_expert, int32_t* __restrict__ expert_offset,
     int32_t* __restrict__ send_count_dev) {
     __shared__ int32_t part_sum[kScanParts][TAMOE_MAX_EXPERTS];
@@ -136,7 +144,7 @@ __global__ __launch_bounds__(kScanThreads) void dispatch_scan_kernel(
             int32_t total = 0;
 #pragma unroll
             for (int pp = 0; pp < kScanParts; ++pp) total += part_sum[pp][e];
-            const int32_t c = cap[e] < 0 ? 0 : cap[e];
+            const int32_t c = pair_limit(cap, e, pad_C);
             kept[e] = total < c ? total : c;
         }
     }
@@ -149,7 +157,8 @@ __global__ __launch_bounds__(kScanThreads) void dispatch_scan_kernel(
 // their own pairs and writes slot[].
 __global__ __launch_bounds__(kThreads) void dispatch_slot_kernel(
     const int32_t* __restrict__ idx, const int32_t* __restrict__ cap, const int32_t* __restrict__ tile_base,
-    const int32_t* __restrict__ expert_offset, int64_t S, int N, int k, int n_ct, int32_t* __restrict__ slot) {
+    const int32_t* __restrict__ expert_offset, int64_t S, int N, int k, int n_ct, int pad_C,
+    int32_t* __restrict__ slot) {
     __shared__ int32_t before[TAMOE_MAX_K * TAMOE_MAX_EXPERTS];
     __shared__ int32_t s_idx[kSlotTile * TAMOE_MAX_K];
 
@@ -172,7 +181,7 @@ __global__ __launch_bounds__(kThreads) void dispatch_slot_kernel(
         if (e >= 0 && e < N) {
             int32_t pos = tile_base[((size_t)j * n_ct + ct) * N + e] + before[j * N + e];
             for (int tt = 0; tt < tl; ++tt) pos += (s_idx[tt * k + j] == e) ? 1 : 0;
-            if (pos < cap[e]) sl = expert_offset[e] + pos;
+            if (pos < pair_limit(cap, e, pad_C)) sl = (pad_C > 0 ? e * pad_C : expert_offset[e]) + pos;
         }
         slot[t0 * k + p] = sl;
     }
@@ -234,6 +243,86 @@ static void launch_copy(const void* x, const int32_t* slot, int64_t S, int k, in
         dispatch_copy_kernel<KK, U, false><<<grid, block, 0, st>>>(src, slot, total, k, cpr, shift, dst);
 }
 
+// Fixed-size layout: zero rows e*C + kept[e] .. (e+1)*C - 1 of every expert, one 16-byte chunk per
+// thread over the whole [N*C, d] buffer; threads of rows that the copy writes leave at once.
+__global__ __launch_bounds__(kThreads) void dispatch_pad_fill_kernel(const int32_t* __restrict__ kept_expert,
+                                                                     int64_t total_chunks, int cpr, int shift, int C,
+                                                                     vec16* __restrict__ send) {
+    const int64_t c = (int64_t)blockIdx.x * kThreads + threadIdx.x;
+    if (c >= total_chunks) return;
+    int row, col;
+    split_chunk(c, total_chunks, cpr, shift, row, col);
+    const int e = row / C;
+    if (row - e * C >= kept_expert[e]) {
+        const vec16 zero = {0u, 0u, 0u, 0u};
+        __builtin_nontemporal_store(zero, send + c);
+    }
+}
+
+// Shared body of tamoe_dispatch (pad_C == 0: packed rows, expert after expert) and
+// tamoe_dispatch_padded (pad_C > 0: pad_C rows per expert, the unused ones zeroed).
+static int dispatch_impl(const char* fn, const void* x, const int32_t* topk_idx, const int32_t* cap, int dtype,
+                         int64_t S, int d, int N, int P, int k, int pad_C, void* send, int32_t* slot,
+                         int32_t* kept_expert, int32_t* expert_offset, int32_t* send_count_dev, void* ws,
+                         size_t ws_bytes, void* stream) {
+    int rc;
+    const Workspace lay = workspace_layout(S, N, k);
+    if (ws_bytes < lay.total)
+        return fail(TAMOE_WORKSPACE_TOO_SMALL, "%s: workspace has %zu bytes, %zu needed", fn, ws_bytes, lay.total);
+    const int64_t n_ct = count_tiles(S);
+    if ((int64_t)k * n_ct > (int64_t)1 << 30)
+        return fail(TAMOE_UNSUPPORTED, "%s: too many count tiles (%lld)", fn, (long long)n_ct);
+    const int cpr = d * elem_bytes(dtype) / 16;  // 16-byte chunks per row
+    if (S > 0 && ceil_div(S * (int64_t)cpr, kThreads * 1) > 0x7fffffff)
+        return fail(TAMOE_UNSUPPORTED, "%s: x is too large for one launch", fn);
+    const int64_t pad_chunks = (int64_t)N * pad_C * cpr;
+    if (ceil_div(pad_chunks, kThreads) > 0x7fffffff)
+        return fail(TAMOE_UNSUPPORTED, "%s: the padded buffer is too large for one launch", fn);
+
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    int32_t* tile_count = reinterpret_cast<int32_t*>(static_cast<char*>(ws) + lay.tile_count);
+
+    if (n_ct > 0) {
+        TraceScope tr("dispatch_count_kernel", st);
+        dispatch_count_kernel<<<dim3((unsigned)n_ct), dim3(kThreads), 0, st>>>(topk_idx, S, N, k, (int)n_ct,
+                                                                                tile_count);
+        if ((rc = check_launch(fn, "dispatch_count_kernel")) != TAMOE_OK) return rc;
+    }
+    {
+        TraceScope tr("dispatch_scan_kernel", st);
+        dispatch_scan_kernel<<<dim3(1), dim3(kScanThreads), 0, st>>>(tile_count, cap, N, P, (int)(k * n_ct), pad_C,
+                                                                      kept_expert, expert_offset, send_count_dev);
+    }
+    if ((rc = check_launch(fn, "dispatch_scan_kernel")) != TAMOE_OK) return rc;
+    if (S > 0) {
+        {
+            TraceScope tr("dispatch_slot_kernel", st);
+            dispatch_slot_kernel<<<dim3((unsigned)ceil_div(S, kSlotTile)), dim3(kThreads), 0, st>>>(
+                topk_idx, cap, tile_count, expert_offset, S, N, k, (int)n_ct, pad_C, slot);
+        }
+        if ((rc = check_launch(fn, "dispatch_slot_kernel")) != TAMOE_OK) return rc;
+        {
+            TraceScope tr("dispatch_copy_kernel", st);
+            if (k == 1)
+                launch_copy<1, 2>(x, slot, S, k, cpr, send, st);
+            else if (k == 2)
+                launch_copy<2, 1>(x, slot, S, k, cpr, send, st);
+            else
+                launch_copy<0, 1>(x, slot, S, k, cpr, send, st);
+        }
+        if ((rc = check_launch(fn, "dispatch_copy_kernel")) != TAMOE_OK) return rc;
+    }
+    if (pad_chunks > 0) {
+        {
+            TraceScope tr("dispatch_pad_fill_kernel", st);
+            dispatch_pad_fill_kernel<<<dim3((unsigned)ceil_div(pad_chunks, kThreads)), dim3(kThreads), 0, st>>>(
+                kept_expert, pad_chunks, cpr, pow2_shift(cpr), pad_C, static_cast<vec16*>(send));
+        }
+        if ((rc = check_launch(fn, "dispatch_pad_fill_kernel")) != TAMOE_OK) return rc;
+    }
+    return TAMOE_OK;
+}
+
 }  // namespace tamoe
 
 using namespace tamoe;
@@ -258,48 +347,29 @@ extern "C" int tamoe_dispatch(const void* x, const int32_t* topk_idx, const int3
         if ((rc = check_ptr(fn, "send", send, 16)) != TAMOE_OK) return rc;
         if ((rc = check_ptr(fn, "slot", slot, 4)) != TAMOE_OK) return rc;
     }
-    const Workspace lay = workspace_layout(S, N, k);
-    if (ws_bytes < lay.total)
-        return fail(TAMOE_WORKSPACE_TOO_SMALL, "%s: workspace has %zu bytes, %zu needed", fn, ws_bytes, lay.total);
-    const int64_t n_ct = count_tiles(S);
-    if ((int64_t)k * n_ct > (int64_t)1 << 30)
-        return fail(TAMOE_UNSUPPORTED, "%s: too many count tiles (%lld)", fn, (long long)n_ct);
-    const int cpr = d * elem_bytes(dtype) / 16;  // 16-byte chunks per row
+    return dispatch_impl(fn, x, topk_idx, cap, dtype, S, d, N, P, k, 0, send, slot, kept_expert, expert_offset,
+                         send_count_dev, ws, ws_bytes, stream);
+}
 
-    hipStream_t st = static_cast<hipStream_t>(stream);
-    int32_t* tile_count = reinterpret_cast<int32_t*>(static_cast<char*>(ws) + lay.tile_count);
-
-    if (n_ct > 0) {
-        TraceScope tr("dispatch_count_kernel", st);
-        dispatch_count_kernel<<<dim3((unsigned)n_ct), dim3(kThreads), 0, st>>>(topk_idx, S, N, k, (int)n_ct,
-                                                                                tile_count);
-        if ((rc = check_launch(fn, "dispatch_count_kernel")) != TAMOE_OK) return rc;
-    }
-    {
-        TraceScope tr("dispatch_scan_kernel", st);
-        dispatch_scan_kernel<<<dim3(1), dim3(kScanThreads), 0, st>>>(tile_count, cap, N, P, (int)(k * n_ct),
-                                                                      kept_expert, expert_offset, send_count_dev);
-    }
-    if ((rc = check_launch(fn, "dispatch_scan_kernel")) != TAMOE_OK) return rc;
+extern "C" int tamoe_dispatch_padded(const void* x, const int32_t* topk_idx, const int32_t* cap, int dtype,
+                                     int64_t S, int d, int N, int P, int k, int C, void* send, int32_t* slot,
+                                     int32_t* kept_expert, void* ws, size_t ws_bytes, void* stream) {
+    const char* fn = "tamoe_dispatch_padded";
+    clear_error();
+    int rc;
+    if ((rc = check_shape(fn, S, N, P, k)) != TAMOE_OK) return rc;
+    if ((rc = check_rows(fn, dtype, d)) != TAMOE_OK) return rc;
+    if (C <= 0 || (int64_t)N * C >= ((int64_t)1 << 31))
+        return fail(TAMOE_INVALID_ARG, "%s: C = %d, N*C must lie in (0, 2^31)", fn, C);
+    if (cap != nullptr && (rc = check_ptr(fn, "cap", cap, 4)) != TAMOE_OK) return rc;
+    if ((rc = check_ptr(fn, "kept_expert", kept_expert, 4)) != TAMOE_OK) return rc;
+    if ((rc = check_ptr(fn, "send", send, 16)) != TAMOE_OK) return rc;
+    if ((rc = check_ptr(fn, "ws", ws, 256)) != TAMOE_OK) return rc;
     if (S > 0) {
-        if (ceil_div(S * (int64_t)cpr, kThreads * 1) > 0x7fffffff)
-            return fail(TAMOE_UNSUPPORTED, "%s: x is too large for one launch", fn);
-        {
-            TraceScope tr("dispatch_slot_kernel", st);
-            dispatch_slot_kernel<<<dim3((unsigned)ceil_div(S, kSlotTile)), dim3(kThreads), 0, st>>>(
-                topk_idx, cap, tile_count, expert_offset, S, N, k, (int)n_ct, slot);
-        }
-        if ((rc = check_launch(fn, "dispatch_slot_kernel")) != TAMOE_OK) return rc;
-        {
-            TraceScope tr("dispatch_copy_kernel", st);
-            if (k == 1)
-                launch_copy<1, 2>(x, slot, S, k, cpr, send, st);
-            else if (k == 2)
-                launch_copy<2, 1>(x, slot, S, k, cpr, send, st);
-            else
-                launch_copy<0, 1>(x, slot, S, k, cpr, send, st);
-        }
-        if ((rc = check_launch(fn, "dispatch_copy_kernel")) != TAMOE_OK) return rc;
+        if ((rc = check_ptr(fn, "x", x, 16)) != TAMOE_OK) return rc;
+        if ((rc = check_ptr(fn, "topk_idx", topk_idx, 4)) != TAMOE_OK) return rc;
+        if ((rc = check_ptr(fn, "slot", slot, 4)) != TAMOE_OK) return rc;
     }
-    return TAMOE_OK;
+    return dispatch_impl(fn, x, topk_idx, cap, dtype, S, d, N, P, k, C, send, slot, kept_expert, nullptr, nullptr,
+                         ws, ws_bytes, stream);
 }

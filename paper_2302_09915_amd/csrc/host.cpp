@@ -259,3 +259,41 @@ extern "C" int tamoe_topo_pattern(const double* beta, const int32_t* level, int 
     }
     return TAMOE_OK;
 }
+
+// Norm variants of the penalty (Section 4.3).  The softmax form works on the reciprocal pattern
+// in units of its own mean, so that `temperature` has the same meaning for every N and S; the
+// largest argument is subtracted before exponentiation.
+extern "C" int tamoe_penalty(const double* c_hat, int N, int norm, double temperature, float* penalty) {
+    const char* fn = "tamoe_penalty";
+    clear_error();
+    if (c_hat == nullptr || penalty == nullptr) return fail(TAMOE_INVALID_ARG, "%s: NULL pointer", fn);
+    if (N <= 0) return fail(TAMOE_INVALID_ARG, "%s: N = %d must be positive", fn, N);
+    if (norm != TAMOE_NORM_L1 && norm != TAMOE_NORM_SOFTMAX)
+        return fail(TAMOE_INVALID_ARG, "%s: unknown norm %d", fn, norm);
+    if (norm == TAMOE_NORM_SOFTMAX && (!(temperature >= 0.0) || !std::isfinite(temperature)))
+        return fail(TAMOE_INVALID_ARG, "%s: temperature must be finite and >= 0", fn);
+    double recip_sum = 0.0;
+    for (int e = 0; e < N; ++e) {
+        if (!(c_hat[e] > 0.0) || !std::isfinite(c_hat[e]))
+            return fail(TAMOE_INVALID_ARG, "%s: c_hat[%d] = %g is not a positive finite number", fn, e, c_hat[e]);
+        recip_sum += 1.0 / c_hat[e];
+    }
+    if (norm == TAMOE_NORM_L1) {
+        for (int e = 0; e < N; ++e) penalty[e] = (float)((1.0 / c_hat[e]) / recip_sum);
+        return TAMOE_OK;
+    }
+    const double scale = temperature * (double)N / recip_sum;  // temperature / mean of the reciprocals
+    std::vector<double> z(N);
+    double top = 0.0;
+    for (int e = 0; e < N; ++e) {
+        z[e] = scale / c_hat[e];
+        top = e == 0 || z[e] > top ? z[e] : top;
+    }
+    double denom = 0.0;
+    for (int e = 0; e < N; ++e) {
+        z[e] = std::exp(z[e] - top);
+        denom += z[e];
+    }
+    for (int e = 0; e < N; ++e) penalty[e] = (float)(z[e] / denom);
+    return TAMOE_OK;
+}

@@ -103,6 +103,25 @@ def test_topo_pattern_rejects_bad_arguments(T):
         call(level=l2)
 
 
+def test_penalty_norms_match_oracle(T, oracle):
+    for name, wl in W.WORKLOADS.items():
+        beta, level = W.topology(wl)
+        c_hat, pen, _ = T.tamoe_topo_pattern(beta, level, wl.P, wl.N, wl.rank, wl.k, wl.S, wl.capacity_factor, 0)
+        np.testing.assert_array_equal(T.tamoe_penalty(c_hat, T.NORM_L1), pen)
+        for tau in (0.0, 0.5, 2.0, 6.0):
+            got = T.tamoe_penalty(c_hat, T.NORM_SOFTMAX, tau)
+            ref = oracle.penalty_softmax(oracle.target_pattern(oracle.smooth_beta(beta, level), wl.N, wl.rank, wl.k,
+                                                               wl.S), tau)
+            assert got.dtype == np.float32
+            np.testing.assert_allclose(got, ref, rtol=2e-7, atol=1e-45, err_msg=f"{name} tau={tau}")
+    with pytest.raises(T.TamoeError) as ei:
+        T.tamoe_penalty(np.array([1.0, 0.0]), T.NORM_SOFTMAX, 1.0)
+    assert ei.value.status == T.INVALID_ARG and "c_hat[1]" in ei.value.message
+    for bad in (dict(norm=3), dict(temperature=-1.0), dict(temperature=float("inf"))):
+        with pytest.raises(T.TamoeError):
+            T.tamoe_penalty(np.array([1.0, 2.0]), bad.get("norm", T.NORM_SOFTMAX), bad.get("temperature", 1.0))
+
+
 # ---- argument checks of the device entry points (they fail before any HIP call) -------------
 def test_device_entry_points_reject_bad_shapes_without_a_gpu(T):
     L = T.lib()
