@@ -321,6 +321,50 @@ def main():
                        "frac_of_hbm_peak": round(rb / (us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)}
             del rout
 
+    # Variants (a further row of the scope): the fixed-size zero-padded layout against the packed one
+    # (bytes written and time of the row movers), and the weight renormalisation.  Untimed pass.
+    variants = None
+    if not args.no_backward:
+        C = int(cap_d.max().item())
+        pad_rows = N * C
+        send_p = torch.empty((pad_rows, d), dtype=x.dtype, device=dev)
+        slot_p = torch.empty_like(slot)
+        kept_p = torch.empty_like(kept)
+        w_n = torch.empty_like(topk_w)
+        d_wn = torch.empty_like(topk_w)
+
+        def var():
+            T.tamoe_dispatch_padded(x, topk_idx, cap_d, N, P, C, send_p, slot_p, kept_p, ws, None)
+            T.tamoe_renorm_topk(topk_w, w_n, None)
+            T.tamoe_renorm_topk_bwd(topk_w, w_n, d_wn, None)
+
+        for _ in range(2):
+            var()
+        torch.cuda.synchronize()
+        reps = 10
+        T.tamoe_trace_start(7 * reps)
+        for _ in range(reps):
+            var()
+        torch.cuda.synchronize()
+        rec = collect()
+        T.tamoe_trace_clear()
+        K_p = int(kept_p.sum().item())
+        live_p = int((slot_p >= 0).any(dim=1).sum().item())
+        us = {n: float(np.mean(ts)) * 1e3 for n, ts in rec.items()}
+        mover_us = us["dispatch_copy_kernel"] + us["dispatch_pad_fill_kernel"]
+        mover_bytes = (live_p + pad_rows) * d * b + S * k * 8
+        variants = {
+            "padded_dispatch": {"C": C, "rows_written": pad_rows, "rows_kept": K_p,
+                                "copy_us": round(us["dispatch_copy_kernel"], 2),
+                                "pad_fill_us": round(us["dispatch_pad_fill_kernel"], 2),
+                                "algo_bytes": int(mover_bytes),
+                                "achieved_GBs": round(mover_bytes / (mover_us * 1e-6) / 1e9, 1),
+                                "rows_vs_packed": round(pad_rows / max(K_p, 1), 4)},
+            "renorm_topk_us": round(us["renorm_topk_kernel"], 2),
+            "renorm_topk_bwd_us": round(us["renorm_topk_bwd_kernel"], 2),
+        }
+        del send_p, slot_p, kept_p, w_n, d_wn
+
     ms_per_step = elapsed * 1e3 / args.steps
     tokens_per_s = S * args.steps / elapsed
 
@@ -386,6 +430,7 @@ def main():
         "kernels": kernels,
         "backward_kernels": backward,
         "regroup_kernel": regroup,
+        "variants": variants,
         "l_topo": float(loss.item()),
         "mode": "graph replay" if args.graph else "eager",
         "kernels_table_from": f"untimed pass of {table_steps} steps with HIP events around every launch",

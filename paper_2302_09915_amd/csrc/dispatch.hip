@@ -17,6 +17,8 @@
 // The copy is bound by HBM: it reads d*b bytes per token with a kept choice and writes d*b
 // bytes per kept pair.  Chunks are laid out flat over the threads, so a wavefront always touches
 // 1 KiB of consecutive bytes, whatever d is.
+#include <algorithm>
+
 #include "internal.h"
 #include "scan128.h"
 
@@ -243,20 +245,19 @@ static void launch_copy(const void* x, const int32_t* slot, int64_t S, int k, in
         dispatch_copy_kernel<KK, U, false><<<grid, block, 0, st>>>(src, slot, total, k, cpr, shift, dst);
 }
 
-// Fixed-size layout: zero rows e*C + kept[e] .. (e+1)*C - 1 of every expert, one 16-byte chunk per
-// thread over the whole [N*C, d] buffer; threads of rows that the copy writes leave at once.
-__global__ __launch_bounds__(kThreads) void dispatch_pad_fill_kernel(const int32_t* __restrict__ kept_expert,
-                                                                     int64_t total_chunks, int cpr, int shift, int C,
-                                                                     vec16* __restrict__ send) {
-    const int64_t c = (int64_t)blockIdx.x * kThreads + threadIdx.x;
-    if (c >= total_chunks) return;
-    int row, col;
-    split_chunk(c, total_chunks, cpr, shift, row, col);
-    const int e = row / C;
-    if (row - e * C >= kept_expert[e]) {
-        const vec16 zero = {0u, 0u, 0u, 0u};
-        __builtin_nontemporal_store(zero, send + c);
-    }
+// Fixed-size layout: zero rows e*C + kept[e] .. (e+1)*C - 1 of every expert.  Workgroup (e, part)
+// clears a contiguous share of expert e's unused chunks: stores only, so nothing waits on memory.
+__global__ __launch_bounds__(kThreads) void dispatch_pad_fill_kernel(const int32_t* __restrict__ kept_expert, int cpr,
+                                                                     int C, vec16* __restrict__ send) {
+    const int e = blockIdx.x;
+    const int32_t used = kept_expert[e];
+    const int64_t n = (int64_t)(C - used) * cpr;                   // chunks to clear, >= 0
+    const int64_t per = (n + gridDim.y - 1) / gridDim.y;
+    const int64_t i0 = (int64_t)blockIdx.y * per;
+    const int64_t i1 = i0 + per < n ? i0 + per : n;
+    vec16* base = send + ((int64_t)e * C + used) * cpr;
+    const vec16 zero = {0u, 0u, 0u, 0u};
+    for (int64_t i = i0 + threadIdx.x; i < i1; i += kThreads) __builtin_nontemporal_store(zero, base + i);
 }
 
 // Shared body of tamoe_dispatch (pad_C == 0: packed rows, expert after expert) and
@@ -275,9 +276,6 @@ static int dispatch_impl(const char* fn, const void* x, const int32_t* topk_idx,
     const int cpr = d * elem_bytes(dtype) / 16;  // 16-byte chunks per row
     if (S > 0 && ceil_div(S * (int64_t)cpr, kThreads * 1) > 0x7fffffff)
         return fail(TAMOE_UNSUPPORTED, "%s: x is too large for one launch", fn);
-    const int64_t pad_chunks = (int64_t)N * pad_C * cpr;
-    if (ceil_div(pad_chunks, kThreads) > 0x7fffffff)
-        return fail(TAMOE_UNSUPPORTED, "%s: the padded buffer is too large for one launch", fn);
 
     hipStream_t st = static_cast<hipStream_t>(stream);
     int32_t* tile_count = reinterpret_cast<int32_t*>(static_cast<char*>(ws) + lay.tile_count);
@@ -312,11 +310,14 @@ static int dispatch_impl(const char* fn, const void* x, const int32_t* topk_idx,
         }
         if ((rc = check_launch(fn, "dispatch_copy_kernel")) != TAMOE_OK) return rc;
     }
-    if (pad_chunks > 0) {
+    if (pad_C > 0) {
         {
+            // about 4096 workgroups in all, at most one per 4 KiB of an expert's rows
+            const int64_t parts = std::max<int64_t>(1, std::min<int64_t>(ceil_div(4096, N),
+                                                                         ceil_div((int64_t)pad_C * cpr, kThreads)));
             TraceScope tr("dispatch_pad_fill_kernel", st);
-            dispatch_pad_fill_kernel<<<dim3((unsigned)ceil_div(pad_chunks, kThreads)), dim3(kThreads), 0, st>>>(
-                kept_expert, pad_chunks, cpr, pow2_shift(cpr), pad_C, static_cast<vec16*>(send));
+            dispatch_pad_fill_kernel<<<dim3((unsigned)N, (unsigned)parts), dim3(kThreads), 0, st>>>(
+                kept_expert, cpr, pad_C, static_cast<vec16*>(send));
         }
         if ((rc = check_launch(fn, "dispatch_pad_fill_kernel")) != TAMOE_OK) return rc;
     }
