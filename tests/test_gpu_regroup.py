@@ -64,3 +64,28 @@ def test_regroup_clips_to_the_buffer_and_rejects_bad_shapes(T):
     assert (o[7:10] == -1).all()                               # their sources lie beyond the buffer
     with pytest.raises(T.TamoeError):
         T.tamoe_regroup(x, torch.zeros((16, 16), dtype=torch.int32, device="cuda"), True, out, None, ws)
+
+
+def test_regroup_at_the_benchmarked_size(T, oracle):
+    """Large-shaped receive buffer (131072 rows of 8 KiB, P = 64 sources x E = 2 local experts), the
+    launch configuration bench.py times; every row compared."""
+    P, E, d, R = 64, 2, 4096, 131072
+    rng = np.random.Generator(np.random.Philox(key=[4, 11]))
+    share = rng.poisson(64, size=(P, E)).astype(np.float64) + 1.0
+    cnt = np.floor(share / share.sum() * R).astype(np.int32)
+    cnt[0, 0] += R - int(cnt.sum())
+    rows = rng.integers(0, 1 << 16, size=(R, d), dtype=np.uint16)      # bit patterns: a pure permutation
+    oracle.set_threads(oracle.max_threads())
+    ref, ref_off = oracle.regroup(rows, W.BF16, cnt, True)
+    x = torch.from_numpy(rows.view(np.int16)).cuda().view(torch.bfloat16)
+    out = torch.empty_like(x)
+    eoff = torch.empty((E + 1,), dtype=torch.int32, device="cuda")
+    ws = T.workspace(1, d, 1, 1, 1, W.BF16)
+    cnt_d = torch.from_numpy(cnt).cuda()
+    T.tamoe_regroup(x, cnt_d, True, out, eoff, ws)
+    torch.cuda.synchronize()
+    assert np.array_equal(to_host(out, W.BF16), ref)
+    np.testing.assert_array_equal(eoff.cpu().numpy(), ref_off)
+    T.tamoe_regroup(out, cnt_d, False, x, None, ws)                      # and back, over the input
+    torch.cuda.synchronize()
+    assert np.array_equal(to_host(x, W.BF16), rows)

@@ -154,3 +154,28 @@ def test_dispatch_padded_empty_and_bad_arguments(T):
     rc = L.tamoe_dispatch_padded(x.data_ptr(), idx.data_ptr(), None, T.F32, 64, 64, 8, 4, 2, 0, send.data_ptr(),
                                  slot.data_ptr(), kept.data_ptr(), ws.data_ptr(), ws.numel(), None)
     assert rc == T.INVALID_ARG and "C = 0" in T.tamoe_last_error()
+
+
+def test_dispatch_padded_at_the_benchmarked_size(T, oracle):
+    """Large: 65536 tokens of 8 KiB, 128 experts, top-2, C = the uniform capacity 1280; slots and every
+    row of the 1.25 GiB buffer compared."""
+    wl = W.WORKLOADS["large"]
+    S, d, N, P, k, C = wl.S, wl.d, wl.N, wl.P, wl.k, 1280
+    oracle.set_threads(oracle.max_threads())
+    idx = W.random_routing(21, S, N, k, skew=0.3)
+    rng = np.random.Generator(np.random.Philox(key=[4, 12]))
+    x_np = rng.integers(0, 1 << 16, size=(S, d), dtype=np.uint16)
+    x_np[x_np == 0] = 1                                                  # no all-zero rows: padding is recognisable
+    x = torch.from_numpy(x_np.view(np.int16)).cuda().view(torch.bfloat16)
+    ws = T.workspace(S, d, N, P, k, wl.dtype)
+    send = torch.full((N * C, d), 3.0, dtype=torch.bfloat16, device="cuda")
+    slot = torch.empty((S, k), dtype=torch.int32, device="cuda")
+    kept = torch.empty((N,), dtype=torch.int32, device="cuda")
+    T.tamoe_dispatch_padded(x, torch.from_numpy(idx).cuda(), None, N, P, C, send, slot, kept, ws)
+    torch.cuda.synchronize()
+    ref_slot, ref_kept = oracle.slots_padded(idx, None, N, C)
+    np.testing.assert_array_equal(slot.cpu().numpy(), ref_slot)
+    np.testing.assert_array_equal(kept.cpu().numpy(), ref_kept)
+    assert ref_kept.max() == C and ref_kept.min() < C                    # some experts overflow, some have padding
+    ref_send = oracle.scatter(x_np, wl.dtype, ref_slot, N * C)
+    assert np.array_equal(to_host(send, wl.dtype), ref_send)
