@@ -66,6 +66,9 @@ def _load():
         "orc_renorm_topk": (None, [c_vp, c_i64, c_i32, c_vp]),
         "orc_renorm_topk_bwd": (None, [c_vp, c_vp, c_i64, c_i32, c_vp]),
         "orc_slots_padded": (None, [c_vp, c_vp, c_i64, c_i32, c_i32, c_i32, c_vp, c_vp]),
+        "orc_minmax_pattern": (c_dbl, [c_vp, c_vp, c_i32, c_i32, c_i32, c_i64, c_dbl, c_vp]),
+        "orc_ring_table": (None, [c_vp, c_vp, c_i32, c_dbl, c_dbl, c_vp, c_vp, c_vp]),
+        "orc_tree_levels": (c_i32, [ctypes.c_char_p, c_i32, c_i32, c_vp, ctypes.c_char_p, c_i32]),
         "orc_regroup": (c_i64, [c_vp, c_i32, c_vp, c_i32, c_i32, c_i32, c_i32, c_vp, c_vp]),
     }
     for name, (res, args) in sig.items():
@@ -139,6 +142,40 @@ def penalty_softmax(c_hat, tau: float) -> np.ndarray:
     out = np.empty_like(c_hat)
     _load().orc_penalty_softmax(_p(c_hat), c_hat.shape[0], float(tau), _p(out))
     return out
+
+
+def minmax_pattern(alpha_row, beta_row, N: int, k: int, S: int, bytes_per_row: float):
+    """Row problem with the latency kept -> (c_hat[N], completion time T)."""
+    beta_row = _c(beta_row, np.float64)
+    alpha_row = None if alpha_row is None else _c(alpha_row, np.float64)
+    P = beta_row.shape[0]
+    assert N % P == 0
+    out = np.empty((N,), dtype=np.float64)
+    T = _load().orc_minmax_pattern(_p(alpha_row), _p(beta_row), P, N, k, S, float(bytes_per_row), _p(out))
+    return out, float(T)
+
+
+def ring_table(beta_link, alpha_link=None, self_beta: float = 1.0, self_alpha: float = 0.0):
+    """-> (beta[P,P], alpha[P,P], level[P,P]) of a ring whose link q joins devices q and q+1."""
+    beta_link = _c(beta_link, np.float64)
+    alpha_link = None if alpha_link is None else _c(alpha_link, np.float64)
+    P = beta_link.shape[0]
+    beta = np.empty((P, P), dtype=np.float64)
+    alpha = np.empty((P, P), dtype=np.float64)
+    level = np.empty((P, P), dtype=np.int32)
+    _load().orc_ring_table(_p(beta_link), _p(alpha_link), P, float(self_beta), float(self_alpha), _p(beta), _p(alpha),
+                           _p(level))
+    return beta, alpha, level
+
+
+def tree_levels(text: str, merge: bool, max_P: int = 1024):
+    """Nested-list tree -> (level[P,P], notation of the labelled tree).  Raises ValueError on bad text."""
+    level = np.empty((max_P * max_P,), dtype=np.int32)
+    buf = ctypes.create_string_buffer(4096)
+    P = _load().orc_tree_levels(text.encode(), 1 if merge else 0, max_P, _p(level), buf, 4096)
+    if P < 0:
+        raise ValueError(f"orc_tree_levels({text!r}) failed with {P}")
+    return level[:P * P].reshape(P, P).copy(), buf.value.decode()
 
 
 def capacity(c_hat, k: int, S: int, cf: float, mode: int) -> np.ndarray:

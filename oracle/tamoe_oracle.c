@@ -22,8 +22,10 @@
  * Every function below is pinned by tests/test_oracle_*.py against closed
  * forms, invariants, brute force, library routines and the worked numbers of
  * the paper's Table 1.  Not pinned ("parity unpinned"): none of the exported
- * functions; the paper's asymmetric-tree merge and global capacity are not
- * implemented here at all.
+ * functions, but two of them restate a reading rather than a definition
+ * of the paper, and their pins are the paper's single example plus invariants:
+ * the merge of asymmetric trees in orc_tree_levels and the arc choice of
+ * orc_ring_table.  Global (cross-device) capacity is not implemented.
  */
 #include <math.h>
 #include <stdint.h>
@@ -243,6 +245,351 @@ double orc_exchange_cost(const double *alpha, const double *beta, const double *
         }
     }
     return worst;
+}
+
+/* ---- topology front-end (host-side setup, Sections 3.2 and 4.2) ---------- */
+
+/*
+ * Target pattern with the latency term kept: the row problem of Section 4.1 / 4.2 for one
+ * sender,  min over v >= 0 with sum_j v[j] = k*S of  max_j ( alpha[j] + beta[j] * bytes * v[j] ),
+ * v[j] = rows sent to device j, shared equally by the E experts of the device.  The optimum
+ * fills the links up to a common completion time T: v[j] = max(0, (T - alpha[j]) / (beta[j] *
+ * bytes)); a link whose latency alone exceeds T carries nothing.  T is found by bisection on the
+ * monotone function sum_j v[j](T) - k*S.  With alpha == NULL (or all zero) this is the closed form
+ * of Section 4.2.  The column constraint (every expert receives k*S/E rows in total) is not
+ * imposed, exactly as in the closed form, where it holds by the symmetry of the table.
+ * Returns T.
+ */
+double orc_minmax_pattern(const double *alpha, const double *beta, int P, int N, int k, int64_t S,
+                          double bytes, double *c_hat)
+{
+    int E = N / P;
+    double total = (double)k * (double)S;
+    double lo = INFINITY, hi = -INFINITY;
+    for (int j = 0; j < P; ++j) {
+        double a = alpha ? alpha[j] : 0.0;
+        if (a < lo)
+            lo = a;
+        if (a + beta[j] * bytes * total > hi)
+            hi = a + beta[j] * bytes * total;
+    }
+    for (int it = 0; it < 400; ++it) {
+        double T = 0.5 * (lo + hi);
+        double rows = 0.0;
+        for (int j = 0; j < P; ++j) {
+            double a = alpha ? alpha[j] : 0.0;
+            if (T > a)
+                rows += (T - a) / (beta[j] * bytes);
+        }
+        if (rows < total)
+            lo = T;
+        else
+            hi = T;
+    }
+    double T = 0.5 * (lo + hi);
+    for (int e = 0; e < N; ++e) {
+        int j = e / E;
+        double a = alpha ? alpha[j] : 0.0;
+        double v = T > a ? (T - a) / (beta[j] * bytes) : 0.0;
+        c_hat[e] = v / (double)E;
+    }
+    return T;
+}
+
+/*
+ * Pairwise tables of a ring (Section 3.2: adjacent devices are joined by links whose bandwidths
+ * may differ; other pairs hop through the devices between them and the slowest link on the way
+ * dominates).  link q joins devices q and (q+1) mod P.  For a pair the two arcs are compared:
+ * the arc with the smaller bottleneck max(beta of its links) is taken, on a tie the one with
+ * fewer hops, then the ascending one.  beta[i][j] = that bottleneck, alpha[i][j] = sum of the
+ * arc's link latencies, level[i][j] = its hop count; the diagonal takes self_beta, self_alpha
+ * and level 0.  alpha_link and alpha may be NULL.
+ */
+void orc_ring_table(const double *beta_link, const double *alpha_link, int P, double self_beta,
+                    double self_alpha, double *beta, double *alpha, int32_t *level)
+{
+    for (int i = 0; i < P; ++i) {
+        for (int j = 0; j < P; ++j) {
+            if (i == j) {
+                beta[i * P + j] = self_beta;
+                if (alpha)
+                    alpha[i * P + j] = self_alpha;
+                level[i * P + j] = 0;
+                continue;
+            }
+            double b_up = 0.0, a_up = 0.0, b_dn = 0.0, a_dn = 0.0;
+            int h_up = 0, h_dn = 0;
+            for (int q = i; q != j; q = (q + 1) % P) {            /* ascending arc: links i .. j-1 */
+                if (beta_link[q] > b_up)
+                    b_up = beta_link[q];
+                a_up += alpha_link ? alpha_link[q] : 0.0;
+                h_up += 1;
+            }
+            for (int q = j; q != i; q = (q + 1) % P) {            /* the other way round: links j .. i-1 */
+                if (beta_link[q] > b_dn)
+                    b_dn = beta_link[q];
+                a_dn += alpha_link ? alpha_link[q] : 0.0;
+                h_dn += 1;
+            }
+            int up = b_up < b_dn || (b_up == b_dn && h_up <= h_dn);
+            beta[i * P + j] = up ? b_up : b_dn;
+            if (alpha)
+                alpha[i * P + j] = up ? a_up : a_dn;
+            level[i * P + j] = up ? h_up : h_dn;
+        }
+    }
+}
+
+/*
+ * Tree topologies in the nested-list notation of Section 3.2 (elements of one sub-list hang off
+ * one switch).  An integer n is a switch with n devices; a list is a switch that joins its
+ * elements.  "[2,2]" is the two-layer symmetric tree of the paper's figure, "[[2,2],[2]]" its
+ * three-layer asymmetric one.  Devices are numbered from left to right.
+ *
+ * Nodes live in flat arrays; a list's children are chained through `next`.
+ */
+#define ORC_MAX_NODES 4096
+typedef struct {
+    int n_dev[ORC_MAX_NODES];   /* > 0: a switch with that many devices; 0: a list */
+    int first[ORC_MAX_NODES];   /* first child of a list, -1 if none */
+    int next[ORC_MAX_NODES];    /* next sibling, -1 at the end */
+    int used;
+    const char *s;              /* parse position */
+    int bad;
+} orc_tree;
+
+static void skip_blank(orc_tree *t)
+{
+    while (*t->s == ' ' || *t->s == '\t')
+        t->s++;
+}
+
+static int parse_element(orc_tree *t)
+{
+    skip_blank(t);
+    if (t->used >= ORC_MAX_NODES) {
+        t->bad = 1;
+        return -1;
+    }
+    int me = t->used++;
+    t->first[me] = -1;
+    t->next[me] = -1;
+    t->n_dev[me] = 0;
+    if (*t->s >= '0' && *t->s <= '9') {
+        long v = 0;
+        while (*t->s >= '0' && *t->s <= '9' && v < 100000)
+            v = v * 10 + (*t->s++ - '0');
+        if (v <= 0 || v >= 100000)
+            t->bad = 1;
+        t->n_dev[me] = (int)v;
+        return me;
+    }
+    if (*t->s != '[') {
+        t->bad = 1;
+        return me;
+    }
+    t->s++;
+    int last = -1;
+    for (;;) {
+        int c = parse_element(t);
+        if (t->bad)
+            return me;
+        if (last < 0)
+            t->first[me] = c;
+        else
+            t->next[last] = c;
+        last = c;
+        skip_blank(t);
+        if (*t->s == ',') {
+            t->s++;
+            continue;
+        }
+        if (*t->s == ']') {
+            t->s++;
+            return me;
+        }
+        t->bad = 1;
+        return me;
+    }
+}
+
+static int tree_height(const orc_tree *t, int v)
+{
+    if (t->n_dev[v] > 0)
+        return 1;
+    int h = 0;
+    for (int c = t->first[v]; c >= 0; c = t->next[c]) {
+        int hc = tree_height(t, c);
+        if (hc > h)
+            h = hc;
+    }
+    return h + 1;
+}
+
+static int child_count(const orc_tree *t, int v)
+{
+    int n = 0;
+    for (int c = t->first[v]; c >= 0; c = t->next[c])
+        n++;
+    return n;
+}
+
+/*
+ * Merge of an asymmetric tree (Section 4.2, last paragraph: separate nodes are merged into the
+ * close symmetric sub-tree; [[2,2],[2]] becomes [[2,2,2]]).  Reading: bottom-up, at every list
+ * whose elements are all lists, an element with fewer members than the largest of its siblings
+ * hands its members to the nearest sibling (the left one on a tie) that has the largest member
+ * count and the same height, and disappears; this is repeated, sub-trees that took members in
+ * included, until the member counts agree (or no sibling qualifies), so that merging the outcome
+ * again changes nothing.
+ */
+static int merge_once(orc_tree *t, int v)
+{
+    int kids[512], size0[512], gone[512];
+    int n = 0, most = 0, moved = 0;
+    for (int c = t->first[v]; c >= 0; c = t->next[c]) {
+        if (t->n_dev[c] > 0 || n >= 512)
+            return 0;                     /* a device switch among the elements: nothing to merge */
+        kids[n++] = c;
+    }
+    for (int i = 0; i < n; ++i) {
+        size0[i] = child_count(t, kids[i]);
+        gone[i] = 0;
+        if (size0[i] > most)
+            most = size0[i];
+    }
+    for (int i = 0; i < n; ++i) {
+        if (size0[i] == most)
+            continue;
+        int target = -1;
+        for (int dist = 1; dist < n && target < 0; ++dist) {
+            int l = i - dist, r = i + dist;
+            if (l >= 0 && size0[l] == most && tree_height(t, kids[l]) == tree_height(t, kids[i]))
+                target = l;
+            else if (r < n && size0[r] == most && tree_height(t, kids[r]) == tree_height(t, kids[i]))
+                target = r;
+        }
+        if (target < 0)
+            continue;
+        int tail = t->first[kids[target]];
+        while (t->next[tail] >= 0)
+            tail = t->next[tail];
+        t->next[tail] = t->first[kids[i]];     /* members move to the end of the target's list */
+        t->first[kids[i]] = -1;
+        gone[i] = 1;
+        moved = 1;
+    }
+    int last = -1;
+    t->first[v] = -1;
+    for (int i = 0; i < n; ++i) {
+        if (gone[i])
+            continue;
+        if (last < 0)
+            t->first[v] = kids[i];
+        else
+            t->next[last] = kids[i];
+        t->next[kids[i]] = -1;
+        last = kids[i];
+    }
+    return moved;
+}
+
+static void merge_tree(orc_tree *t, int v)
+{
+    if (t->n_dev[v] > 0)
+        return;
+    do {                                  /* a sub-tree that took members in is looked at again */
+        for (int c = t->first[v]; c >= 0; c = t->next[c])
+            merge_tree(t, c);
+    } while (merge_once(t, v));
+}
+
+static int count_devices(const orc_tree *t, int v)
+{
+    if (t->n_dev[v] > 0)
+        return t->n_dev[v];
+    int n = 0;
+    for (int c = t->first[v]; c >= 0; c = t->next[c])
+        n += count_devices(t, c);
+    return n;
+}
+
+/* level labels of all pairs with both devices below v; devices of v are base .. base+count-1 */
+static void label_pairs(const orc_tree *t, int v, int base, int P, int32_t *level)
+{
+    int h = tree_height(t, v);
+    int n = count_devices(t, v);
+    /* every pair below v gets v's height first; deeper switches overwrite their own pairs */
+    for (int i = base; i < base + n; ++i)
+        for (int j = base; j < base + n; ++j)
+            level[i * P + j] = i == j ? 0 : h;
+    if (t->n_dev[v] > 0)
+        return;
+    int b = base;
+    for (int c = t->first[v]; c >= 0; c = t->next[c]) {
+        label_pairs(t, c, b, P, level);
+        b += count_devices(t, c);
+    }
+}
+
+static int print_tree(const orc_tree *t, int v, char *out, int len, int pos)
+{
+    if (t->n_dev[v] > 0) {
+        char buf[16];
+        int m = 0, x = t->n_dev[v];
+        while (x > 0) {
+            buf[m++] = (char)('0' + x % 10);
+            x /= 10;
+        }
+        while (m > 0 && pos < len - 1)
+            out[pos++] = buf[--m];
+        return pos;
+    }
+    if (pos < len - 1)
+        out[pos++] = '[';
+    for (int c = t->first[v]; c >= 0; c = t->next[c]) {
+        pos = print_tree(t, c, out, len, pos);
+        if (t->next[c] >= 0 && pos < len - 1)
+            out[pos++] = ',';
+    }
+    if (pos < len - 1)
+        out[pos++] = ']';
+    return pos;
+}
+
+/*
+ * Level table of a tree topology: level[i][j] = height of the lowest switch that joins devices i
+ * and j (1: the same device switch, 2: one layer up, ...), 0 on the diagonal.  With merge != 0 the
+ * tree is merged first (see merge_tree).  `text_out` (may be NULL) receives the notation of the
+ * tree that was labelled.  Returns the number of devices P, -1 on a syntax error, -2 if P > max_P.
+ */
+int orc_tree_levels(const char *text, int merge, int max_P, int32_t *level, char *text_out,
+                    int text_len)
+{
+    orc_tree *t = (orc_tree *)malloc(sizeof(orc_tree));
+    t->used = 0;
+    t->s = text;
+    t->bad = 0;
+    int root = parse_element(t);
+    skip_blank(t);
+    if (t->bad || *t->s != '\0') {
+        free(t);
+        return -1;
+    }
+    if (merge)
+        merge_tree(t, root);
+    int P = count_devices(t, root);
+    if (P > max_P) {
+        free(t);
+        return -2;
+    }
+    label_pairs(t, root, 0, P, level);
+    if (text_out != NULL && text_len > 0) {
+        int pos = print_tree(t, root, text_out, text_len, 0);
+        text_out[pos] = '\0';
+    }
+    free(t);
+    return P;
 }
 
 /* ---- gate: scores, softmax, top-k ---------------------------------------- */

@@ -90,6 +90,72 @@ __global__ __launch_bounds__(kThreads) void combine_bwd_kernel(const vec16* __re
     }
 }
 
+// ---- combine backward, rows of 64 * 2^n chunks (1 KiB .. 16 KiB), k <= 2 --------------------------
+// One 16-byte chunk per thread, no loop: like the forward row movers, the thread issues its loads
+// (dy and the k source rows), then its k stores.  A token's row spans cpr / 64 whole wavefronts of
+// one workgroup; the dot products are reduced by a butterfly inside the wavefront and then summed
+// over the row's wavefronts in ascending order by the row's first lane (fixed order).
+template <int DT, int KK, int WG>
+__global__ __launch_bounds__(WG) void combine_bwd_flat_kernel(const vec16* __restrict__ dy,
+                                                              const vec16* __restrict__ recv, int64_t K_rows,
+                                                              const int32_t* __restrict__ slot,
+                                                              const float* __restrict__ topk_w, int64_t S, int shift,
+                                                              vec16* __restrict__ d_recv, float* __restrict__ d_w) {
+    __shared__ float part[WG / 64][KK];
+    const int cpr = 1 << shift;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int64_t c = (int64_t)blockIdx.x * WG + threadIdx.x;
+    const int64_t tok = c >> shift;  // the same for the whole wavefront: cpr >= 64
+    const bool live = tok < S;
+    const int t = __builtin_amdgcn_readfirstlane(live ? (int)tok : 0);
+    const int col = (int)c & (cpr - 1);
+    int32_t s[KK];
+    float w[KK], dot[KK];
+#pragma unroll
+    for (int j = 0; j < KK; ++j) {
+        const int32_t sj = live ? slot[(int64_t)t * KK + j] : -1;
+        s[j] = (sj >= 0 && (int64_t)sj < K_rows) ? sj : -1;
+        w[j] = topk_w[(int64_t)t * KK + j];
+        dot[j] = 0.f;
+    }
+    if (live) {
+        const vec16 g = __builtin_nontemporal_load(dy + c);
+        vec16 r[KK];
+#pragma unroll
+        for (int j = 0; j < KK; ++j)
+            if (s[j] >= 0) r[j] = __builtin_nontemporal_load(recv + (size_t)s[j] * cpr + col);
+#pragma unroll
+        for (int j = 0; j < KK; ++j) {
+            if (s[j] < 0) continue;
+            dot[j] = chunk_dot<DT>(g, r[j], 0.f);
+            float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+            Chunk<DT>::fma(acc, w[j], g);
+            __builtin_nontemporal_store(Chunk<DT>::pack(acc), d_recv + (size_t)s[j] * cpr + col);
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < KK; ++j) {
+        float v = dot[j];
+        v += __shfl_xor(v, 32);
+        v += __shfl_xor(v, 16);
+        v += __shfl_xor(v, 8);
+        v += __shfl_xor(v, 4);
+        v += __shfl_xor(v, 2);
+        v += __shfl_xor(v, 1);
+        if (lane == 0) part[wave][j] = v;
+    }
+    __syncthreads();
+    const int wpr = cpr >> 6;  // wavefronts per row
+    if (live && lane == 0 && (wave & (wpr - 1)) == 0) {
+#pragma unroll
+        for (int j = 0; j < KK; ++j) {
+            float v = 0.f;
+            for (int i = 0; i < wpr; ++i) v += part[wave + i][j];
+            d_w[(int64_t)t * KK + j] = s[j] >= 0 ? v : 0.f;
+        }
+    }
+}
+
 // ---- gate backward ------------------------------------------------------------------------------
 // value of lane (lane ^ MASK), MASK < 32, through the LDS crossbar
 template <int MASK>
@@ -209,6 +275,21 @@ static void launch_combine_bwd(const void* dy, const void* recv, int64_t K_rows,
     const vec16* r = static_cast<const vec16*>(recv);
     vec16* o = static_cast<vec16*>(d_recv);
     TraceScope tr("combine_bwd_kernel", st);
+    const int shift = pow2_shift(cpr);
+    if (k <= 2 && shift >= 6 && shift <= 10) {
+        // rows of 1, 2, 4 KiB share a 256-thread workgroup; 8 and 16 KiB rows take one of their own
+        const int wg = cpr <= 256 ? 256 : cpr;
+        const dim3 fgrid((unsigned)ceil_div(S * (int64_t)cpr, wg)), fblock(wg);
+#define TAMOE_FLAT(KK, WG) \
+    combine_bwd_flat_kernel<DT, KK, WG><<<fgrid, fblock, 0, st>>>(g, r, K_rows, slot, topk_w, S, shift, o, d_w)
+        if (k == 1) {
+            if (wg == 256) TAMOE_FLAT(1, 256); else if (wg == 512) TAMOE_FLAT(1, 512); else TAMOE_FLAT(1, 1024);
+        } else {
+            if (wg == 256) TAMOE_FLAT(2, 256); else if (wg == 512) TAMOE_FLAT(2, 512); else TAMOE_FLAT(2, 1024);
+        }
+#undef TAMOE_FLAT
+        return;
+    }
     if (k == 1)
         combine_bwd_kernel<DT, 1><<<grid, block, 0, st>>>(g, r, K_rows, slot, topk_w, S, k, cpr, o, d_w);
     else if (k == 2)

@@ -87,7 +87,10 @@ def test_gate_bwd(T, oracle, S, N, P, k, use_penalty):
 
 @pytest.mark.parametrize("dtype,S,d,k,frac", [
     (W.BF16, 3000, 136, 2, 0.8), (W.BF16, 700, 4096, 2, 1.0), (W.BF16, 5000, 512, 1, 0.5),
-    (W.F32, 900, 36, 3, 0.7), (W.BF16, 333, 1032, 5, 0.6), (W.F32, 1, 4, 1, 1.0)])
+    (W.F32, 900, 36, 3, 0.7), (W.BF16, 333, 1032, 5, 0.6), (W.F32, 1, 4, 1, 1.0),
+    # rows of 2^n KiB with k <= 2 take the one-chunk-per-thread kernel: 2, 8 and 16 KiB rows, a last
+    # workgroup that is partly empty, both storage types
+    (W.BF16, 1001, 1024, 2, 0.7), (W.F32, 513, 2048, 2, 0.9), (W.BF16, 131, 8192, 1, 0.8), (W.F32, 67, 256, 2, 0.5)])
 def test_combine_bwd_and_dispatch_bwd(T, oracle, dtype, S, d, k, frac):
     oracle.set_threads(oracle.max_threads())
     rng = np.random.default_rng(S + d)
