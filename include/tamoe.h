@@ -107,6 +107,43 @@ int tamoe_topo_pattern(const double* beta, const int32_t* level, int P, int N, i
  */
 int tamoe_penalty(const double* c_hat, int N, int norm, double temperature, float* penalty);
 
+/*
+ * Topology front-end, host only: tables for tamoe_topo_pattern from a description of the network
+ * (Section 3.2: ring, symmetric and asymmetric tree in nested-list notation; Section 4.2).
+ *
+ * tamoe_tree_levels: `tree` is the paper's nested list as text: an integer n is a switch with n
+ * devices, a list "[a,b,...]" a switch that joins its elements ("[2,2]": 2 switches x 2 devices;
+ * "[[2,2],[2]]": the asymmetric 3-layer example).  Devices are numbered left to right.
+ * level[i*P+j] = height of the lowest switch that joins devices i and j (1 = same device switch),
+ * 0 on the diagonal: the labels tamoe_topo_pattern smooths over.  merge_asymmetric != 0 first merges
+ * the tree (Section 4.2, last paragraph: "[[2,2],[2]]" becomes "[[2,2,2]]"): bottom-up, at every
+ * list whose elements are all lists, an element with fewer members than the largest one hands its
+ * members to the nearest largest sibling of the same height (the left one on a tie), repeatedly,
+ * until nothing moves.  The paper shows the one example; the rule is this library's reading.
+ * level: room for max_P*max_P ints; *P_out = devices found; tree_out (may be NULL): the tree that
+ * was labelled, as text.
+ *
+ * tamoe_ring_table: link q joins devices q and (q+1) mod P (inverse bandwidth beta_link[q] > 0,
+ * latency alpha_link[q] >= 0 or alpha_link == NULL).  Other pairs hop over the devices between
+ * them and the slowest link of the way dominates (Section 3.2): of the two arcs the one with the
+ * smaller largest beta is used, on a tie the shorter, then the ascending one.  beta[i][j] = that
+ * largest beta, alpha[i][j] (alpha may be NULL) = sum of the arc's latencies, level[i][j] = hops;
+ * the diagonal gets self_beta, self_alpha, level 0.  All tables [P*P].
+ *
+ * tamoe_minmax_pattern: the exchange problem of Section 4.1 / 4.2 for one sender with the latency
+ * term kept:  minimise over v >= 0, sum_j v_j = k*S:  max_j ( alpha_row[j] + beta_row[j] *
+ * bytes_per_row * v_j ),  solved exactly; c_hat[e] = v_{e/E} / E, *t_comm (may be NULL) = the
+ * optimum.  With alpha_row == NULL or constant it returns the closed form that
+ * tamoe_topo_pattern uses.  The balance constraint across senders is not imposed (as in the
+ * closed form, where it holds by symmetry of the table).
+ */
+int tamoe_tree_levels(const char* tree, int merge_asymmetric, int max_P, int32_t* level, int* P_out,
+                      char* tree_out, size_t tree_out_len);
+int tamoe_ring_table(const double* beta_link, const double* alpha_link, int P, double self_beta,
+                     double self_alpha, double* beta, double* alpha, int32_t* level);
+int tamoe_minmax_pattern(const double* alpha_row, const double* beta_row, int P, int N, int k, int64_t S,
+                         double bytes_per_row, double* c_hat, double* t_comm);
+
 /* Bytes of device workspace that any of the device functions below needs for this shape. */
 size_t tamoe_workspace_bytes(int64_t S, int d, int N, int P, int k, int dtype);
 

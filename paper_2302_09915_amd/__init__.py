@@ -35,6 +35,7 @@ EXPORTS = (
     "tamoe_version", "tamoe_last_error", "tamoe_topo_pattern", "tamoe_workspace_bytes",
     "tamoe_gate", "tamoe_select", "tamoe_aux_loss", "tamoe_dispatch", "tamoe_combine",
     "tamoe_gate_bwd", "tamoe_combine_bwd", "tamoe_dispatch_bwd", "tamoe_regroup",
+    "tamoe_tree_levels", "tamoe_ring_table", "tamoe_minmax_pattern",
     "tamoe_penalty", "tamoe_renorm_topk", "tamoe_renorm_topk_bwd", "tamoe_dispatch_padded",
     "tamoe_trace_start", "tamoe_trace_filter", "tamoe_trace_stop", "tamoe_trace_get", "tamoe_trace_clear", "tamoe_copy_probe", "tamoe_mix_probe",
 )
@@ -48,6 +49,7 @@ class TamoeError(RuntimeError):
 
 
 _lib = None
+dbl_t = ctypes.c_double
 
 
 def lib() -> ctypes.CDLL:
@@ -85,6 +87,12 @@ def lib() -> ctypes.CDLL:
     L.tamoe_dispatch_bwd.argtypes = [vp, i64, vp, i32, i64, i32, i32, vp, vp]
     L.tamoe_regroup.restype = i32
     L.tamoe_regroup.argtypes = [vp, vp, i32, i32, i32, i32, i64, i32, vp, vp, vp, sz, vp]
+    L.tamoe_tree_levels.restype = i32
+    L.tamoe_tree_levels.argtypes = [ctypes.c_char_p, i32, i32, vp, ctypes.POINTER(ctypes.c_int), ctypes.c_char_p, sz]
+    L.tamoe_ring_table.restype = i32
+    L.tamoe_ring_table.argtypes = [vp, vp, i32, dbl, dbl, vp, vp, vp]
+    L.tamoe_minmax_pattern.restype = i32
+    L.tamoe_minmax_pattern.argtypes = [vp, vp, i32, i32, i32, i64, dbl, vp, ctypes.POINTER(dbl)]
     L.tamoe_penalty.restype = i32
     L.tamoe_penalty.argtypes = [vp, i32, i32, dbl, vp]
     L.tamoe_renorm_topk.restype = i32
@@ -178,6 +186,53 @@ def tamoe_topo_pattern(beta, level, P: int, N: int, rank: int, k: int, S: int, c
         c_hat.ctypes.data_as(ctypes.c_void_p), pen.ctypes.data_as(ctypes.c_void_p),
         cap.ctypes.data_as(ctypes.c_void_p)))
     return c_hat, pen, cap
+
+
+def _host(a, dt):
+    return None if a is None else np.ascontiguousarray(a, dtype=dt)
+
+
+def _hp(a):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def tamoe_tree_levels(tree: str, merge_asymmetric: bool, max_P: int = 1024):
+    """Host.  Nested-list text -> (level i32[P,P], text of the labelled tree)."""
+    level = np.empty(max_P * max_P, dtype=np.int32)
+    P = ctypes.c_int(0)
+    buf = ctypes.create_string_buffer(max(4096, 4 * len(tree) + 16))
+    _check(lib().tamoe_tree_levels(tree.encode(), 1 if merge_asymmetric else 0, max_P, _hp(level), ctypes.byref(P),
+                                   buf, len(buf)))
+    n = P.value
+    return level[:n * n].reshape(n, n).copy(), buf.value.decode()
+
+
+def tamoe_ring_table(beta_link, alpha_link=None, self_beta: float = 1.0, self_alpha: float = 0.0):
+    """Host.  Link tables of a ring -> (beta f64[P,P], alpha f64[P,P], level i32[P,P])."""
+    bl = _host(beta_link, np.float64)
+    al = _host(alpha_link, np.float64)
+    P = bl.shape[0]
+    if al is not None and al.shape != bl.shape:
+        raise TamoeError(INVALID_ARG, "alpha_link must have the shape of beta_link")
+    beta = np.empty((P, P), dtype=np.float64)
+    alpha = np.empty((P, P), dtype=np.float64)
+    level = np.empty((P, P), dtype=np.int32)
+    _check(lib().tamoe_ring_table(_hp(bl), _hp(al), P, float(self_beta), float(self_alpha), _hp(beta), _hp(alpha),
+                                  _hp(level)))
+    return beta, alpha, level
+
+
+def tamoe_minmax_pattern(alpha_row, beta_row, N: int, k: int, S: int, bytes_per_row: float):
+    """Host.  Row problem with latency -> (c_hat f64[N], optimum T)."""
+    br = _host(beta_row, np.float64)
+    ar = _host(alpha_row, np.float64)
+    P = br.shape[0]
+    if ar is not None and ar.shape != br.shape:
+        raise TamoeError(INVALID_ARG, "alpha_row must have the shape of beta_row")
+    c_hat = np.empty(max(int(N), 0), dtype=np.float64)
+    T = dbl_t(0.0)
+    _check(lib().tamoe_minmax_pattern(_hp(ar), _hp(br), P, N, k, S, float(bytes_per_row), _hp(c_hat), ctypes.byref(T)))
+    return c_hat, T.value
 
 
 def tamoe_penalty(c_hat, norm: int, temperature: float = 1.0) -> np.ndarray:
