@@ -358,13 +358,16 @@ void gate_bf16_kernel(
             dst[u] = (!KTAIL || in) ? t : zero;
         }
     };
+    // x is read with ordinary loads, not streaming (nontemporal) ones, although the gate uses every
+    // byte once: an ordinary load leaves the line in the 256 MB last-level cache, and the dispatch
+    // reads x again right after the gate.  On a 512 MiB x the scatter gets about half of its reads
+    // from that cache (its kernel 307 -> 256 us) for 5 us more here.
     auto load_x = [&](int kc, vec16 (&dst)[XU]) {
         kc = chunk_at(kc);
         int k0 = kc * kKC;
         if constexpr (KTAIL) k0 = (k0 + piece * 8 < d) ? k0 : d - 8 - piece * 8;
 #pragma unroll
-        for (int u = 0; u < XU; ++u)
-            dst[u] = __builtin_nontemporal_load(reinterpret_cast<const vec16*>(xsrc[u] + k0));
+        for (int u = 0; u < XU; ++u) dst[u] = *reinterpret_cast<const vec16*>(xsrc[u] + k0);
     };
     auto store_w = [&](const vec16 (&src)[WU], int buf) {
 #pragma unroll
