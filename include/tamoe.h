@@ -13,6 +13,13 @@
  *   tamoe_aux_loss      topology-aware auxiliary loss l_topo (or the plain l_aux)
  *   tamoe_dispatch      capacity-limited slot assignment + scatter into the send buffer
  *   tamoe_combine       weighted gather of the returned rows into y
+ * and around them
+ *   tamoe_gate_bwd, tamoe_combine_bwd, tamoe_dispatch_bwd   backward of the path
+ *   tamoe_regroup       received rows regrouped per local expert (and back)
+ *   tamoe_penalty, tamoe_renorm_topk(_bwd), tamoe_dispatch_padded   variants: Norm of the penalty,
+ *                       renormalised weights, fixed-size zero-padded send layout
+ *   tamoe_tree_levels, tamoe_ring_table, tamoe_minmax_pattern   host: topology front-end
+ *   tamoe_trace_*, tamoe_copy_probe, tamoe_mix_probe   measurement aids, not steps of the path
  *
  * The global exchange, the experts and the return exchange sit between tamoe_dispatch and
  * tamoe_combine and are not part of this library.

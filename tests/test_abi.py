@@ -170,6 +170,32 @@ def test_device_entry_points_reject_bad_shapes_without_a_gpu(T):
     status(L.tamoe_combine(one, 10, one, one, 1, 64, 64, 0, one, None), T.INVALID_ARG, "k = 0")
     status(L.tamoe_combine(one, 10, one, one, 1, 64, 64, 2, None, None), T.INVALID_ARG, "y is NULL")
     status(L.tamoe_combine(one, 10, one, one, 0, 64, 6, 2, one, None), T.UNSUPPORTED, "16 bytes")
+    # backward
+    status(L.tamoe_combine_bwd(one, one, 10, one, one, 1, 64, 64, 9, one, one, None), T.UNSUPPORTED, "k = 9 exceeds")
+    status(L.tamoe_combine_bwd(one, one, -1, one, one, 1, 64, 64, 2, one, one, None), T.INVALID_ARG, "negative")
+    status(L.tamoe_combine_bwd(one, one, 10, one, one, 1, 64, 64, 2, one, None, None), T.INVALID_ARG, "d_topk_w is NULL")
+    status(L.tamoe_gate_bwd(one, one, one, None, one, 1.0, 64, 8, 3, 1, one, None), T.INVALID_ARG, "not a multiple of P")
+    status(L.tamoe_gate_bwd(one, one, one, None, one, 1.0, 64, 8, 4, 1, None, None), T.INVALID_ARG, "d_logits is NULL")
+    status(L.tamoe_dispatch_bwd(one, 10, one, 1, 64, 60, 2, one, None), T.UNSUPPORTED, "16 bytes")
+    # regroup
+    status(L.tamoe_regroup(one, one, 0, 2, 1, 64, 10, 1, one, None, one, big, None), T.INVALID_ARG, "must be positive")
+    status(L.tamoe_regroup(one, one, 64, 4, 1, 64, 10, 1, one, None, one, big, None), T.UNSUPPORTED, "exceeds the limit of 128")
+    status(L.tamoe_regroup(one, one, 4, 2, 1, 64, -1, 1, one, None, one, big, None), T.INVALID_ARG, "cap_rows")
+    status(L.tamoe_regroup(one, one, 4, 2, 1, 64, 10, 1, one, None, one, 8, None), T.WORKSPACE_TOO_SMALL, "needed")
+    status(L.tamoe_regroup(one, one, 4, 2, 1, 60, 10, 1, one, None, one, big, None), T.UNSUPPORTED, "16 bytes")
+    # variants
+    status(L.tamoe_renorm_topk(one, 64, 0, one, None), T.INVALID_ARG, "k = 0")
+    status(L.tamoe_renorm_topk(one, 64, 9, one, None), T.UNSUPPORTED, "k = 9 exceeds")
+    status(L.tamoe_renorm_topk(one, 64, 2, None, None), T.INVALID_ARG, "out is NULL")
+    status(L.tamoe_renorm_topk_bwd(one, None, 64, 2, one, None), T.INVALID_ARG, "d_out is NULL")
+    status(L.tamoe_dispatch_padded(one, one, None, 1, 64, 64, 8, 4, 2, 0, one, one, one, one, big, None),
+           T.INVALID_ARG, "C = 0")
+    status(L.tamoe_dispatch_padded(one, one, None, 1, 64, 64, 8, 4, 2, 1 << 29, one, one, one, one, big, None),
+           T.INVALID_ARG, "N*C")
+    status(L.tamoe_dispatch_padded(one, one, None, 1, 64, 64, 8, 4, 2, 16, None, one, one, one, big, None),
+           T.INVALID_ARG, "send is NULL")
+    status(L.tamoe_dispatch_padded(one, one, None, 1, 64, 64, 8, 4, 2, 16, one, one, one, one, 0, None),
+           T.WORKSPACE_TOO_SMALL, "needed")
 
 
 def test_workspace_size_is_monotone_and_covers_the_configs(T):
