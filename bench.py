@@ -78,22 +78,46 @@ def cpu_baseline(wl, W, seconds: float):
 
     def run(S):
         inp = W.make_inputs(wl, S=S)
-        t0 = time.perf_counter()
+        steps = {}
+        t_start = t0 = time.perf_counter()
+
+        def lap(name):
+            nonlocal t0
+            t1 = time.perf_counter()
+            steps[name] = round(t1 - t0, 4)
+            t0 = t1
+
         c_hat, p, cap = oracle.setup(beta, level, wl.N, wl.rank, wl.k, S, wl.capacity_factor, 0)
+        lap("setup")
         lg = oracle.logits(inp["x"], inp["w"], wl.dtype)
+        lap("scores")
         r = oracle.route_from_logits(lg, wl.k, wl.P, p, cap)
+        lap("softmax_topk_counts_losses_slots")
         send = oracle.scatter(inp["x"], wl.dtype, r["slot"], r["K"])
+        lap("scatter")
         oracle.combine(send, wl.dtype, r["slot"], r["topk_w"], want_exact=False, want_rounded=True)
-        return time.perf_counter() - t0
+        lap("combine")
+        return time.perf_counter() - t_start, steps
 
     probe_S = min(wl.S, 256)
-    t_probe = run(probe_S)
+    t_probe, _ = run(probe_S)
     S = int(min(wl.S, max(probe_S, seconds / max(t_probe, 1e-6) * probe_S)))
     S = max(64, S // 64 * 64) if wl.S >= 64 else wl.S
-    t = run(S)
-    return {"value": S / t, "unit": "tokens/s", "cores": threads, "kind": "oracle",
-            "sample": f"first-draw sample of {S} of {wl.S} tokens of workload {wl.name}, whole path "
-                      f"(setup, scores, softmax, top-k, counts, losses, slots, scatter, combine), {t:.2f} s"}
+    t, steps = run(S)
+    out = {"value": S / t, "unit": "tokens/s", "cores": threads, "kind": "oracle",
+           "sample": f"first-draw sample of {S} of {wl.S} tokens of workload {wl.name}, whole path "
+                     f"(setup, scores, softmax, top-k, counts, losses, slots, scatter, combine), {t:.2f} s",
+           "per_step_seconds": steps}
+    if threads > 1:
+        # the same oracle on one thread, on a sample sized to a few seconds
+        oracle.set_threads(1)
+        S1 = int(min(S, max(probe_S, 4.0 / max(t, 1e-6) * S / threads)))
+        S1 = max(64, S1 // 64 * 64) if wl.S >= 64 else wl.S
+        t1, steps1 = run(S1)
+        oracle.set_threads(threads)
+        out["single_thread"] = {"value": S1 / t1, "unit": "tokens/s", "cores": 1,
+                                "sample": f"first-draw sample of {S1} tokens, {t1:.2f} s", "per_step_seconds": steps1}
+    return out
 
 
 def main():
@@ -245,6 +269,34 @@ def main():
     dominant_live = collect().get(dominant) if traced_in_timed_region else None
     T.tamoe_trace_filter(None)
     T.tamoe_trace_clear()
+
+    # The other capacity mode beside the headline one (uniform <-> proportional to the target pattern):
+    # a short timed region of its own, same buffers; restored afterwards.
+    other_mode = None
+    if not args.graph:
+        K_main = int(off[-1].item())
+        _, _, cap_o = T.tamoe_topo_pattern(beta, level, wl.P, wl.N, wl.rank, wl.k, wl.S, wl.capacity_factor,
+                                           1 - args.cap_mode)
+        cap_keep = cap_d.clone()
+        cap_d.copy_(torch.from_numpy(cap_o).to(dev))
+        n_o = max(1, min(args.steps, 20))
+        for _ in range(2):
+            step()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(n_o):
+            step()
+        torch.cuda.synchronize()
+        el_o = time.perf_counter() - t0
+        K_o = int(off[-1].item())
+        other_mode = {"cap_mode": 1 - args.cap_mode, "steps": n_o, "ms_per_step": round(el_o * 1e3 / n_o, 4),
+                      "value": round(S * n_o / el_o, 1), "unit": "tokens/s", "kept_rows_K": K_o,
+                      "drop_rate": round(1.0 - K_o / (S * k), 4)}
+        cap_d.copy_(cap_keep)
+        for _ in range(rotate):                  # slot, send and the size outputs are those of the headline mode again
+            step()
+        torch.cuda.synchronize()
+        assert int(off[-1].item()) == K_main
 
     # Backward kernels (the next row of the scope after the forward path): measured in a pass of
     # their own with events around every launch; they are not part of `value`.
@@ -431,6 +483,7 @@ def main():
         "backward_kernels": backward,
         "regroup_kernel": regroup,
         "variants": variants,
+        "other_capacity_mode": other_mode,
         "l_topo": float(loss.item()),
         "mode": "graph replay" if args.graph else "eager",
         "kernels_table_from": f"untimed pass of {table_steps} steps with HIP events around every launch",
