@@ -23,10 +23,12 @@ void clear_error() { g_err[0] = '\0'; }
 
 int gate_waves(int64_t S, int N) {
     // eight wavefronts (one workgroup per compute unit, 256 CUs) halve the traffic of W once
-    // there are enough tokens; otherwise aim for at least two workgroups per compute unit
+    // there are enough tokens; otherwise aim for two workgroups per compute unit, except that two
+    // wavefronts sharing a W tile beat single-wavefront workgroups as soon as every compute unit
+    // gets one (16384 tokens: 15.2 -> 13.3 us at d = 1024, 21.4 -> 18.6 us at d = 2048)
     if (N > 32 && ceil_div(S, 256) >= 256) return 8;
     if (ceil_div(S, 128) >= 512) return 4;
-    if (ceil_div(S, 64) >= 512) return 2;
+    if (ceil_div(S, 64) >= 256) return 2;
     return 1;
 }
 
