@@ -2,17 +2,20 @@
 // destination-grouped send buffer (paper Section 3.1: dispatched data [k*S, d], local capacity;
 // Section 4.1: one merged delivery per destination device; Section 4.3: variable chunk sizes).
 //
-// Four launches, no atomics on positions, so the result is the same on every run:
+// Four launches (five for the fixed-size padded layout), no atomics on positions, so the result is
+// the same on every run:
 //   1. dispatch_count_kernel  pairs per (choice j, count tile of 1024 tokens, expert)
 //   2. dispatch_scan_kernel   exclusive prefix of those counts in priority order (choice-major,
 //                             then token order), kept = min(count, cap), expert offsets, rows per
 //                             destination device
 //   3. dispatch_slot_kernel   one workgroup per 64 tokens: recount the pairs of the count tile
 //                             that precede them, rank the 64 tokens' own pairs, write slot[]
-//   4. dispatch_copy_kernel   streams the rows: each thread owns four 16-byte chunks of x, reads
-//                             a chunk once if its token has a kept choice and stores it to each
-//                             of the token's slots.  No loop and no LDS: like a plain copy, the
-//                             latency of HBM is covered by the number of independent wavefronts.
+//   4. dispatch_copy_kernel   streams the rows: each thread owns one 16-byte chunk of x (two for
+//                             k = 1), reads it once if its token has a kept choice and stores it
+//                             to each of the token's slots.  No loop and no LDS: like a plain
+//                             copy, the latency of HBM is covered by the number of independent
+//                             wavefronts.
+//   5. dispatch_pad_fill_kernel (tamoe_dispatch_padded only) zeroes every expert's unused rows.
 //
 // The copy is bound by HBM: it reads d*b bytes per token with a kept choice and writes d*b
 // bytes per kept pair.  Chunks are laid out flat over the threads, so a wavefront always touches
