@@ -237,6 +237,36 @@ def test_odd_shapes(T, oracle, dtype, S, d, N, P, k, cf):
     full_parity(T, oracle, {"dtype": dtype, "N": N, "P": P, "k": k}, x, w, pen.astype(np.float64), cap)
 
 
+def _random_shape(i):
+    """Seeded random shape inside the library's limits: ragged S, d any multiple of 16 bytes, any N % P == 0."""
+    rng = np.random.default_rng(1000 + i)
+    dtype = W.BF16 if i % 4 else W.F32
+    P = int(rng.choice([1, 2, 3, 4, 6, 8, 16, 32, 64]))
+    E = int(rng.integers(1, max(2, 128 // P + 1)))
+    N = P * E
+    k = int(rng.integers(1, min(N, 8) + 1))
+    S = int(rng.choice([rng.integers(1, 300), rng.integers(300, 5000), rng.integers(5000, 40000)]))
+    unit = 8 if dtype == W.BF16 else 4
+    d = unit * int(rng.choice([rng.integers(1, 9), rng.integers(9, 80), rng.integers(80, 300)]))
+    if S * d > 6_000_000:                                   # keep the oracle's fp64 score product to seconds
+        S = max(1, 6_000_000 // d)
+    cf = float(rng.choice([0.5, 1.0, 1.25, 2.0]))
+    return dtype, S, d, N, P, k, cf
+
+
+@pytest.mark.parametrize("i", range(24))
+def test_random_shapes(T, oracle, i):
+    dtype, S, d, N, P, k, cf = _random_shape(i)
+    print(f"shape {i}: dtype={dtype} S={S} d={d} N={N} P={P} k={k} cf={cf}", flush=True)
+    oracle.set_threads(oracle.max_threads())
+    rng = np.random.default_rng(2000 + i)
+    x = W.to_storage(rng.standard_normal((S, d)).astype(np.float32), dtype)
+    w = W.to_storage((rng.standard_normal((N, d)) / math.sqrt(d)).astype(np.float32), dtype)
+    beta = rng.uniform(1.0, 9.0, size=(P, P))
+    c_hat, pen, cap = T.tamoe_topo_pattern(beta, None, P, N, int(rng.integers(P)), k, S, cf, i % 2)
+    full_parity(T, oracle, {"dtype": dtype, "N": N, "P": P, "k": k}, x, w, pen.astype(np.float64), cap)
+
+
 def test_empty_input(T):
     N, P, k, d = 8, 4, 2, 64
     x = torch.empty((0, d), dtype=torch.bfloat16, device="cuda")
