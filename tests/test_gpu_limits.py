@@ -1,0 +1,81 @@
+"""Sizes beyond what the oracle can follow on the CPU: a token matrix of more than 2^32 16-byte
+chunks (64 GiB), where the kernels' chunk indices need 64 bits.  Inputs are seeded and generated on
+the device; the results are checked through properties that hold at any size (kept counts, the slot
+permutation, token order inside an expert, bit-exact rows, the one-term combine), evaluated with
+plain tensor operations on the device."""
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+@pytest.fixture(scope="module")
+def T():
+    if not torch.cuda.is_available():
+        pytest.fail("these tests need a GPU")
+    import paper_2302_09915_amd as T
+
+    T.lib()
+    return T
+
+
+def test_more_than_2_to_32_chunks(T):
+    dev = torch.device("cuda:0")
+    if torch.cuda.mem_get_info()[0] < 215 * 2 ** 30:
+        pytest.skip("needs 215 GiB of free device memory (three 64 GiB matrices)")
+    S, d, N, P, k = (1 << 21) + 3, 16384, 8, 8, 1
+    assert S * d * 2 // 16 > 1 << 32
+    g = torch.Generator(device=dev)
+    g.manual_seed(7)
+    x = torch.empty((S, d), dtype=torch.bfloat16, device=dev)
+    for s0 in range(0, S, 1 << 16):
+        n = min(1 << 16, S - s0)
+        x[s0:s0 + n] = torch.randn((n, d), generator=g, device=dev, dtype=torch.float32).to(torch.bfloat16)
+    idx = torch.randint(0, N, (S, k), generator=g, device=dev, dtype=torch.int32)
+    w = torch.rand((S, k), generator=g, device=dev, dtype=torch.float32) + 0.25
+    cap = torch.full((N,), S, dtype=torch.int32, device=dev)
+    cap[3] = 1000                                        # one expert drops most of its pairs
+    ws = T.workspace(S, d, N, P, k, T.BF16, dev)
+    send = torch.empty((S * k, d), dtype=torch.bfloat16, device=dev)
+    slot = torch.empty((S, k), dtype=torch.int32, device=dev)
+    kept = torch.empty((N,), dtype=torch.int32, device=dev)
+    off = torch.empty((N + 1,), dtype=torch.int32, device=dev)
+    scd = torch.empty((P,), dtype=torch.int32, device=dev)
+    T.tamoe_dispatch(x, idx, cap, N, P, send, slot, kept, off, scd, ws, None)
+    torch.cuda.synchronize()
+
+    cnt = torch.bincount(idx.flatten().long(), minlength=N)
+    exp_kept = torch.minimum(cnt, cap.long())
+    assert torch.equal(kept.long(), exp_kept)
+    assert torch.equal(off.long(), torch.cat([torch.zeros(1, dtype=torch.long, device=dev), exp_kept.cumsum(0)]))
+    assert torch.equal(scd.long(), exp_kept)              # one expert per device
+    K = int(off[-1].item())
+    live = slot[:, 0] >= 0
+    assert int(live.sum().item()) == K
+    sl = slot[:, 0][live].long()
+    assert int(sl.max().item()) == K - 1 and torch.unique(sl).numel() == K      # a permutation of 0..K-1
+    for e in (0, 3, 7):                                   # token order inside an expert, drops at the end
+        s_e = slot[:, 0][idx[:, 0] == e]
+        n_e = int(exp_kept[e].item())
+        assert bool((s_e[:n_e] >= 0).all()) and bool((s_e[n_e:] < 0).all())
+        assert torch.equal(s_e[:n_e].long(), torch.arange(int(off[e].item()), int(off[e].item()) + n_e, device=dev))
+    tok = torch.nonzero(live).flatten()
+    bad = 0
+    for s0 in range(0, tok.numel(), 1 << 14):             # every kept row arrived bit-exact
+        t = tok[s0:s0 + (1 << 14)]
+        bad += int((send[slot[t, 0].long()].view(torch.int16) != x[t].view(torch.int16)).any(dim=1).sum().item())
+    assert bad == 0
+
+    y = torch.empty((S, d), dtype=torch.bfloat16, device=dev)
+    T.tamoe_combine(send, K, slot, w, y, None)
+    torch.cuda.synchronize()
+    bad = 0
+    for s0 in range(0, S, 1 << 14):                       # k = 1: y = round(w * x), zero row for a dropped token
+        n = min(1 << 14, S - s0)
+        ref = (w[s0:s0 + n, :1] * x[s0:s0 + n].float()).to(torch.bfloat16)
+        ref = torch.where(live[s0:s0 + n, None], ref, torch.zeros_like(ref))
+        bad += int((ref.view(torch.int16) != y[s0:s0 + n].view(torch.int16)).any(dim=1).sum().item())
+    assert bad == 0
+    del x, send, y
+    torch.cuda.empty_cache()
