@@ -40,6 +40,38 @@ def test_every_declared_symbol_is_exported(T):
     assert T.tamoe_version() == 1
 
 
+def test_header_is_plain_c(tmp_path):
+    """The boundary is a C ABI: the header must compile as C99 and as C++ with no torch or HIP types,
+    and a C program must link against the library through it."""
+    import shutil
+    import subprocess
+
+    hdr = os.path.join(ROOT, "include", "tamoe.h")
+    for cc, std, lang in (("gcc", "-std=c99", "c"), ("g++", "-std=c++11", "c++")):
+        if shutil.which(cc) is None:
+            pytest.skip(f"{cc} not found")
+        subprocess.run([cc, std, "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only", "-x", lang, hdr], check=True)
+    text = open(hdr).read()
+    assert "#include <hip" not in text and "torch" not in text
+    src = tmp_path / "use.c"
+    src.write_text('#include "tamoe.h"\n#include <stdio.h>\n'
+                   'int main(void) { double c[2] = {1.0, 3.0}; float p[2];\n'
+                   '  if (tamoe_version() != TAMOE_VERSION) return 1;\n'
+                   '  if (tamoe_penalty(c, 2, TAMOE_NORM_L1, 0.0, p) != TAMOE_OK) return 2;\n'
+                   '  if (tamoe_penalty(c, 0, TAMOE_NORM_L1, 0.0, p) != TAMOE_INVALID_ARG) return 3;\n'
+                   '  printf("%.2f %.2f %s\\n", p[0], p[1], tamoe_last_error()); return 0; }\n')
+    import paper_2302_09915_amd as pkg
+    libdir = os.path.dirname(pkg.LIB_PATH)
+    exe = tmp_path / "use"
+    r = subprocess.run(["gcc", "-std=c99", "-I", os.path.join(ROOT, "include"), str(src), "-L", libdir, "-ltamoe",
+                        f"-Wl,-rpath,{libdir}", "-o", str(exe)], capture_output=True, text=True)
+    if r.returncode != 0:
+        pytest.skip("cannot link a C program against libtamoe here: " + r.stderr[-300:])
+    out = subprocess.run([str(exe)], capture_output=True, text=True)
+    assert out.returncode == 0, out.stderr
+    assert out.stdout.startswith("0.75 0.25 tamoe_penalty")
+
+
 def test_limits_match_header(T):
     text = open(os.path.join(ROOT, "include", "tamoe.h")).read()
     assert int(re.search(r"#define TAMOE_MAX_EXPERTS (\d+)", text).group(1)) == T.MAX_EXPERTS
