@@ -120,11 +120,14 @@ extern "C" int tamoe_regroup(const void* in, const int32_t* recv_count, int P, i
     if ((rc = check_launch(fn, "regroup_offsets_kernel")) != TAMOE_OK) return rc;
     if (cap_rows == 0) return TAMOE_OK;
     const int cpr = d * elem_bytes(dtype) / 16;
-    const int64_t blocks = ceil_div(cap_rows * cpr, kThreads);
+    // two chunks per thread: the offset tables are loaded once per 8 KiB instead of once per 4 KiB
+    // (2 GiB: 377 -> 341 us; four chunks: 350 us)
+    constexpr int kChunksPerThread = 2;
+    const int64_t blocks = ceil_div(cap_rows * cpr, kThreads * kChunksPerThread);
     if (blocks > 0x7fffffff) return fail(TAMOE_UNSUPPORTED, "%s: the buffer is too large for one launch", fn);
     {
         TraceScope tr("regroup_copy_kernel", st);
-        regroup_copy_kernel<1><<<dim3((unsigned)blocks), dim3(kThreads), 0, st>>>(
+        regroup_copy_kernel<kChunksPerThread><<<dim3((unsigned)blocks), dim3(kThreads), 0, st>>>(
             static_cast<const vec16*>(in), tables, P, E, cap_rows, cpr, pow2_shift(cpr), to_expert_major ? 1 : 0,
             static_cast<vec16*>(out));
     }
