@@ -41,7 +41,8 @@ def parse_args():
     ap.add_argument("--workload", default="large")
     ap.add_argument("--cap-mode", type=int, default=0, help="0 uniform capacity, 1 proportional to the target pattern")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-backward", action="store_true", help="skip the (untimed) measurement of the backward kernels")
+    ap.add_argument("--no-extras", "--no-backward", dest="no_extras", action="store_true",
+                    help="skip the measurements beside the forward path (backward kernels, regrouping, variants)")
     ap.add_argument("--no-trace", action="store_true",
                     help="no HIP events inside the timed region (per-kernel times then come from an extra traced pass)")
     ap.add_argument("--graph", action="store_true",
@@ -120,6 +121,263 @@ def cpu_baseline(wl, W, seconds: float):
     return out
 
 
+def _mean_us(ts) -> float:
+    return float(np.mean(ts)) * 1e3
+
+
+def _median_us(T, n_rec: int) -> float:
+    return float(np.median([T.tamoe_trace_get(i)[1] for i in range(n_rec)])) * 1e3
+
+
+def _rate(nbytes: float, us: float) -> dict:
+    gbs = nbytes / (us * 1e-6) / 1e9
+    return {"algo_bytes": int(nbytes), "achieved_GBs": round(gbs, 1), "frac_of_hbm_peak": round(gbs / HBM_PEAK_GBS, 4)}
+
+
+class Path:
+    """The buffers of one workload on the device and one step of the path over them."""
+
+    def __init__(self, T, W, torch, wl, cap_mode: int, rotate: int):
+        self.T, self.W, self.torch, self.wl = T, W, torch, wl
+        self.dev = dev = torch.device("cuda:0")
+        torch.cuda.set_device(dev)
+        inp = W.make_inputs(wl)
+        self.beta, self.level = W.topology(wl)
+        _, pen, cap = T.tamoe_topo_pattern(self.beta, self.level, wl.P, wl.N, wl.rank, wl.k, wl.S, wl.capacity_factor,
+                                           cap_mode)
+        self.x, self.w = self._upload(inp["x"]), self._upload(inp["w"])
+        S, d, N, P, k = wl.S, wl.d, wl.N, wl.P, wl.k
+        self.row_bytes = d * wl.elem_bytes
+        i32, f32 = torch.int32, torch.float32
+        self.pen = torch.from_numpy(pen).to(dev)
+        self.cap = torch.from_numpy(cap).to(dev)
+        self.ws = T.workspace(S, d, N, P, k, wl.dtype, dev)
+        self.topk_idx = torch.empty((S, k), dtype=i32, device=dev)
+        self.topk_w = torch.empty((S, k), dtype=f32, device=dev)
+        self.m = torch.empty((N,), dtype=f32, device=dev)
+        self.c_expert = torch.empty((N,), dtype=i32, device=dev)
+        self.c_device = torch.empty((P,), dtype=i32, device=dev)
+        self.loss = torch.empty((1,), dtype=f32, device=dev)
+        self.send = torch.empty((S * k, d), dtype=self.x.dtype, device=dev)
+        self.slot = torch.empty((S, k), dtype=i32, device=dev)
+        self.kept = torch.empty((N,), dtype=i32, device=dev)
+        self.off = torch.empty((N + 1,), dtype=i32, device=dev)
+        self.scd = torch.empty((P,), dtype=i32, device=dev)
+        self.y = torch.empty((S, d), dtype=self.x.dtype, device=dev)
+        self.rotate = rotate
+        self.sets = [(self.x, self.send, self.y)] + [
+            (self.x.clone(), torch.empty_like(self.send), torch.empty_like(self.y)) for _ in range(rotate - 1)]
+        self.turn = 0
+
+    def _upload(self, a):
+        t = self.torch.from_numpy(a)
+        if self.wl.dtype == self.W.BF16:
+            t = t.view(self.torch.int16).view(self.torch.bfloat16)
+        return t.to(self.dev)
+
+    def step(self):
+        T, wl = self.T, self.wl
+        xs, sends, ys = self.sets[self.turn % self.rotate]
+        self.turn += 1
+        # stream=None: the binding passes torch's current stream (the capture stream under --graph)
+        T.tamoe_gate(xs, self.w, wl.P, wl.k, None, self.topk_idx, self.topk_w, self.m, self.c_expert, self.c_device,
+                     self.ws, None)
+        T.tamoe_aux_loss(self.m, self.c_expert, self.pen, wl.P, wl.S, self.loss, None)
+        T.tamoe_dispatch(xs, self.topk_idx, self.cap, wl.N, wl.P, sends, self.slot, self.kept, self.off, self.scd,
+                         self.ws, None)
+        # identity expert: the rows come back as they were sent; S*k bounds the row count
+        T.tamoe_combine(sends, wl.S * wl.k, self.slot, self.topk_w, ys, None)
+
+    def sync(self):
+        self.torch.cuda.synchronize()
+
+    def kept_rows(self) -> int:
+        return int(self.off[-1].item())
+
+    def live_tokens(self) -> int:
+        return int((self.slot >= 0).any(dim=1).sum().item())
+
+    def collect(self) -> dict:
+        """Stops the trace; kernel name -> list of durations in ms."""
+        out = {}
+        for i in range(self.T.tamoe_trace_stop()):
+            name, ms = self.T.tamoe_trace_get(i)
+            out.setdefault(name, []).append(ms)
+        return out
+
+
+def measure_probes(p: Path):
+    """Yardsticks outside the timed region: a plain copy of x into y, and (k = 2, rows a multiple of
+    1 KiB) the scatter's and the combine's bare memory operations on the realised slot table."""
+    T, wl = p.T, p.wl
+    S, k, row = wl.S, wl.k, p.row_bytes
+    T.tamoe_trace_start(16)
+    for _ in range(5):
+        T.tamoe_copy_probe(p.x, p.y, p.torch.cuda.current_stream())
+    copy_us = _median_us(T, T.tamoe_trace_stop())
+    copy_gbs = 2.0 * S * row / (copy_us * 1e-6) / 1e9
+    copy = {"bytes_moved": int(2 * S * row), "median_us": round(copy_us, 2), "GBs": round(copy_gbs, 1),
+            "frac_of_hbm_peak": round(copy_gbs / HBM_PEAK_GBS, 4)}
+    mix = None
+    if k == 2 and row % 1024 == 0:
+        r0 = p.slot[:, 0].contiguous()
+        r1 = p.slot[:, 1].contiguous()
+        T.tamoe_trace_start(16)
+        for _ in range(5):
+            T.tamoe_mix_probe(p.x, p.send, r0, r1, 1, None)
+        sc_us = _median_us(T, T.tamoe_trace_stop())
+        T.tamoe_trace_start(16)
+        for _ in range(5):
+            T.tamoe_mix_probe(p.send, p.y, r0, r1, 2, None)
+        ga_us = _median_us(T, T.tamoe_trace_stop())
+        K0 = int((p.slot >= 0).sum().item())
+        mix = {"scatter_1r2w": {"median_us": round(sc_us, 2),
+                                "GBs": round((p.live_tokens() + K0) * row / (sc_us * 1e-6) / 1e9, 1)},
+               "gather_2r1w": {"median_us": round(ga_us, 2), "GBs": round((K0 + S) * row / (ga_us * 1e-6) / 1e9, 1)}}
+    return copy, mix
+
+
+def measure_other_mode(p: Path, cap_mode: int, steps: int):
+    """The other capacity mode beside the headline one (uniform <-> proportional to the target
+    pattern): a short timed region of its own on the same buffers; the headline state is restored."""
+    T, wl, torch = p.T, p.wl, p.torch
+    K_main = p.kept_rows()
+    _, _, cap_o = T.tamoe_topo_pattern(p.beta, p.level, wl.P, wl.N, wl.rank, wl.k, wl.S, wl.capacity_factor,
+                                       1 - cap_mode)
+    cap_keep = p.cap.clone()
+    p.cap.copy_(torch.from_numpy(cap_o).to(p.dev))
+    n = max(1, min(steps, 20))
+    for _ in range(2):
+        p.step()
+    p.sync()
+    t0 = time.perf_counter()
+    for _ in range(n):
+        p.step()
+    p.sync()
+    elapsed = time.perf_counter() - t0
+    K_o = p.kept_rows()
+    p.cap.copy_(cap_keep)
+    for _ in range(p.rotate):                    # slot, send and the size outputs are those of the headline mode again
+        p.step()
+    p.sync()
+    assert p.kept_rows() == K_main
+    return {"cap_mode": 1 - cap_mode, "steps": n, "ms_per_step": round(elapsed * 1e3 / n, 4),
+            "value": round(wl.S * n / elapsed, 1), "unit": "tokens/s", "kept_rows_K": K_o,
+            "drop_rate": round(1.0 - K_o / (wl.S * wl.k), 4)}
+
+
+def measure_backward(p: Path):
+    """Backward kernels: a pass of their own with events around every launch; not part of `value`."""
+    T, wl, torch = p.T, p.wl, p.torch
+    S, d, N, P, k, row = wl.S, wl.d, wl.N, wl.P, wl.k, p.row_bytes
+    K_now = p.kept_rows()
+    logits = torch.empty((S, N), dtype=torch.float32, device=p.dev)
+    T.tamoe_gate(p.x, p.w, P, k, logits, p.topk_idx, p.topk_w, p.m, p.c_expert, p.c_device, p.ws, None)
+    dy = p.y                                     # any tensor of the shape of y serves as upstream gradient
+    d_recv = torch.empty((max(K_now, 1), d), dtype=p.x.dtype, device=p.dev)
+    d_w = torch.empty((S, k), dtype=torch.float32, device=p.dev)
+    d_logits = torch.empty((S, N), dtype=torch.float32, device=p.dev)
+    d_x = torch.empty((S, d), dtype=p.x.dtype, device=p.dev)
+
+    def bwd():
+        T.tamoe_combine_bwd(dy, p.send, K_now, p.slot, p.topk_w, d_recv, d_w, None)
+        T.tamoe_gate_bwd(logits, p.topk_idx, d_w, p.pen, p.c_expert, 1.0, P, d_logits, None)
+        T.tamoe_dispatch_bwd(d_recv, K_now, p.slot, d_x, None)
+
+    for _ in range(3):
+        bwd()
+    p.sync()
+    reps = 10
+    T.tamoe_trace_start(3 * reps)
+    for _ in range(reps):
+        bwd()
+    p.sync()
+    rec = p.collect()
+    T.tamoe_trace_clear()
+    nbytes = {"combine_bwd_kernel": S * row + 2 * K_now * row + S * k * 12,
+              "gate_bwd_kernel": 2 * S * N * 4 + S * k * 8,
+              "dispatch_bwd_kernel": K_now * row + S * row + S * k * 4}
+    return [{"kernel": name, "avg_us": round(_mean_us(ts), 2), **_rate(nbytes[name], _mean_us(ts))}
+            for name, ts in rec.items()]
+
+
+def measure_regroup(p: Path):
+    """Receive-side regrouping: the kept rows of `send` stand in for a receive buffer with P source
+    chunks x E local experts (E = 2 when the workload has one expert per device, where regrouping is
+    the identity), seeded Poisson segment sizes.  Not part of `value`."""
+    T, wl, torch = p.T, p.wl, p.torch
+    E_r = wl.E if wl.E > 1 else 2
+    P_r = min(wl.P, 128 // E_r)
+    rows = p.kept_rows()
+    if rows < P_r * E_r:
+        return None
+    rng = np.random.Generator(np.random.Philox(key=[wl.seed, 11]))
+    share = rng.poisson(64, size=(P_r, E_r)).astype(np.float64) + 1.0
+    cnt = np.floor(share / share.sum() * rows).astype(np.int32)
+    cnt[0, 0] += rows - int(cnt.sum())
+    cnt_d = torch.from_numpy(cnt).to(p.dev)
+    rin = p.send[:rows]
+    rout = torch.empty_like(rin)
+    for _ in range(2):
+        T.tamoe_regroup(rin, cnt_d, True, rout, None, p.ws, None)
+    p.sync()
+    T.tamoe_trace_filter("regroup_copy_kernel")
+    T.tamoe_trace_start(10)
+    for _ in range(10):
+        T.tamoe_regroup(rin, cnt_d, True, rout, None, p.ws, None)
+    p.sync()
+    rec = p.collect()
+    T.tamoe_trace_filter(None)
+    T.tamoe_trace_clear()
+    us = _mean_us(rec["regroup_copy_kernel"])
+    return {"kernel": "regroup_copy_kernel", "P": P_r, "E": E_r, "rows": rows, "avg_us": round(us, 2),
+            **_rate(2 * rows * p.row_bytes, us)}
+
+
+def measure_variants(p: Path):
+    """The fixed-size zero-padded layout against the packed one (rows written, time of the row
+    movers) and the weight renormalisation.  Not part of `value`."""
+    T, wl, torch = p.T, p.wl, p.torch
+    S, d, N, P, k, row = wl.S, wl.d, wl.N, wl.P, wl.k, p.row_bytes
+    C = int(p.cap.max().item())
+    pad_rows = N * C
+    send_p = torch.empty((pad_rows, d), dtype=p.x.dtype, device=p.dev)
+    slot_p = torch.empty_like(p.slot)
+    kept_p = torch.empty_like(p.kept)
+    w_n = torch.empty_like(p.topk_w)
+    d_wn = torch.empty_like(p.topk_w)
+
+    def var():
+        T.tamoe_dispatch_padded(p.x, p.topk_idx, p.cap, N, P, C, send_p, slot_p, kept_p, p.ws, None)
+        T.tamoe_renorm_topk(p.topk_w, w_n, None)
+        T.tamoe_renorm_topk_bwd(p.topk_w, w_n, d_wn, None)
+
+    for _ in range(2):
+        var()
+    p.sync()
+    reps = 10
+    T.tamoe_trace_start(7 * reps)
+    for _ in range(reps):
+        var()
+    p.sync()
+    us = {n: _mean_us(ts) for n, ts in p.collect().items()}
+    T.tamoe_trace_clear()
+    K_p = int(kept_p.sum().item())
+    live_p = int((slot_p >= 0).any(dim=1).sum().item())
+    mover_us = us["dispatch_copy_kernel"] + us["dispatch_pad_fill_kernel"]
+    mover_bytes = (live_p + pad_rows) * row + S * k * 8
+    return {
+        "padded_dispatch": {"C": C, "rows_written": pad_rows, "rows_kept": K_p,
+                            "copy_us": round(us["dispatch_copy_kernel"], 2),
+                            "pad_fill_us": round(us["dispatch_pad_fill_kernel"], 2),
+                            "algo_bytes": int(mover_bytes),
+                            "achieved_GBs": round(mover_bytes / (mover_us * 1e-6) / 1e9, 1),
+                            "rows_vs_packed": round(pad_rows / max(K_p, 1), 4)},
+        "renorm_topk_us": round(us["renorm_topk_kernel"], 2),
+        "renorm_topk_bwd_us": round(us["renorm_topk_bwd_kernel"], 2),
+    }
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -137,122 +395,37 @@ def main():
         sys.exit(2)
     T.lib()
     wl = W.WORKLOADS[args.workload]
-    dev = torch.device("cuda:0")
-    torch.cuda.set_device(dev)
-
-    inp = W.make_inputs(wl)
-    beta, level = W.topology(wl)
-    c_hat, pen, cap = T.tamoe_topo_pattern(beta, level, wl.P, wl.N, wl.rank, wl.k, wl.S, wl.capacity_factor,
-                                           args.cap_mode)
-
-    def up(a):
-        t = torch.from_numpy(a)
-        if wl.dtype == W.BF16:
-            t = t.view(torch.int16).view(torch.bfloat16)
-        return t.to(dev)
-
-    x, w = up(inp["x"]), up(inp["w"])
-    del inp
-    S, d, N, P, k = wl.S, wl.d, wl.N, wl.P, wl.k
-    b = wl.elem_bytes
-    pen_d = torch.from_numpy(pen).to(dev)
-    cap_d = torch.from_numpy(cap).to(dev)
-    ws = T.workspace(S, d, N, P, k, wl.dtype, dev)
-    i32, f32 = torch.int32, torch.float32
-    topk_idx = torch.empty((S, k), dtype=i32, device=dev)
-    topk_w = torch.empty((S, k), dtype=f32, device=dev)
-    m = torch.empty((N,), dtype=f32, device=dev)
-    c_expert = torch.empty((N,), dtype=i32, device=dev)
-    c_device = torch.empty((P,), dtype=i32, device=dev)
-    loss = torch.empty((1,), dtype=f32, device=dev)
-    send = torch.empty((S * k, d), dtype=x.dtype, device=dev)
-    slot = torch.empty((S, k), dtype=i32, device=dev)
-    kept = torch.empty((N,), dtype=i32, device=dev)
-    off = torch.empty((N + 1,), dtype=i32, device=dev)
-    scd = torch.empty((P,), dtype=i32, device=dev)
-    y = torch.empty((S, d), dtype=x.dtype, device=dev)
-    stream = torch.cuda.current_stream()
-    rotate = max(1, args.rotate)
-    sets = [(x, send, y)] + [(x.clone(), torch.empty_like(send), torch.empty_like(y)) for _ in range(rotate - 1)]
-    turn = [0]
-
-    def step():
-        xs, sends, ys = sets[turn[0] % rotate]
-        turn[0] += 1
-        # stream=None: the binding passes torch's current stream (the capture stream under --graph)
-        T.tamoe_gate(xs, w, P, k, None, topk_idx, topk_w, m, c_expert, c_device, ws, None)
-        T.tamoe_aux_loss(m, c_expert, pen_d, P, S, loss, None)
-        T.tamoe_dispatch(xs, topk_idx, cap_d, N, P, sends, slot, kept, off, scd, ws, None)
-        # identity expert: the rows come back as they were sent; S*k bounds the row count
-        T.tamoe_combine(sends, S * k, slot, topk_w, ys, None)
+    p = Path(T, W, torch, wl, args.cap_mode, max(1, args.rotate))
+    S, N, k, row = wl.S, wl.N, wl.k, p.row_bytes
 
     for _ in range(max(args.warmup, 0)):
-        step()
-    torch.cuda.synchronize()
-
-    # yardstick, outside the timed region: a plain copy of x into y (same size)
-    T.tamoe_trace_start(16)
-    for _ in range(5):
-        T.tamoe_copy_probe(x, y, stream)
-    n_rec = T.tamoe_trace_stop()
-    copy_us = float(np.median([T.tamoe_trace_get(i)[1] for i in range(n_rec)])) * 1e3
-    copy_gbs = 2.0 * S * d * b / (copy_us * 1e-6) / 1e9
-
-    # row-mix yardsticks on the realised slot table (k = 2, rows a multiple of 1 KiB): the scatter's
-    # and the combine's memory operations with nothing else around them
-    mix = None
-    if k == 2 and (d * b) % 1024 == 0:
-        r0 = slot[:, 0].contiguous()
-        r1 = slot[:, 1].contiguous()
-        T.tamoe_trace_start(16)
-        for _ in range(5):
-            T.tamoe_mix_probe(x, send, r0, r1, 1, None)
-        n_rec = T.tamoe_trace_stop()
-        sc_us = float(np.median([T.tamoe_trace_get(i)[1] for i in range(n_rec)])) * 1e3
-        T.tamoe_trace_start(16)
-        for _ in range(5):
-            T.tamoe_mix_probe(send, y, r0, r1, 2, None)
-        n_rec = T.tamoe_trace_stop()
-        ga_us = float(np.median([T.tamoe_trace_get(i)[1] for i in range(n_rec)])) * 1e3
-        K0 = int((slot >= 0).sum().item())
-        live0 = int((slot >= 0).any(dim=1).sum().item())
-        mix = {"scatter_1r2w": {"median_us": round(sc_us, 2),
-                                "GBs": round((live0 + K0) * d * b / (sc_us * 1e-6) / 1e9, 1)},
-               "gather_2r1w": {"median_us": round(ga_us, 2),
-                               "GBs": round((K0 + S) * d * b / (ga_us * 1e-6) / 1e9, 1)}}
-
-    launches_per_step = 9
-
-    def collect():
-        n = T.tamoe_trace_stop()
-        out = {}
-        for i in range(n):
-            name, ms = T.tamoe_trace_get(i)
-            out.setdefault(name, []).append(ms)
-        return out
+        p.step()
+    p.sync()
+    copy_probe, mix_probe = measure_probes(p)
 
     # Pass 1 (not timed): every launch bracketed by HIP events -> the per-kernel table and the name
     # of the longest-running kernel.  Two event records per launch cost ~3 us of GPU time each, so
     # this pass is kept out of `value`.
+    launches_per_step = 9
     table_steps = max(1, min(args.steps, 20))
     T.tamoe_trace_filter(None)
     T.tamoe_trace_start(launches_per_step * table_steps)
     for _ in range(table_steps):
-        step()
-    torch.cuda.synchronize()
-    per_kernel = collect()
+        p.step()
+    p.sync()
+    per_kernel = p.collect()
     dominant = max(per_kernel, key=lambda n: float(np.mean(per_kernel[n])))
 
-    run_step = step
+    run_step = p.step
     if args.graph:
         # the library only enqueues kernels on the current stream, so a step can be captured as is
         graph = torch.cuda.CUDAGraph()
         with torch.cuda.graph(graph):
-            step()                               # with --rotate the replays reuse the captured set
+            p.step()                             # with --rotate the replays reuse the captured set
         run_step = graph.replay
         for _ in range(2):
             run_step()
-        torch.cuda.synchronize()
+        p.sync()
 
     # Pass 2, the timed region: K steps; only the dominant kernel is bracketed by events (two
     # records per step), which is what `roofline.achieved` is computed from.
@@ -260,170 +433,28 @@ def main():
     if traced_in_timed_region:
         T.tamoe_trace_filter(dominant)
         T.tamoe_trace_start(args.steps)
-    torch.cuda.synchronize()
+    p.sync()
     t0 = time.perf_counter()
     for _ in range(args.steps):
         run_step()
-    torch.cuda.synchronize()
+    p.sync()
     elapsed = time.perf_counter() - t0
-    dominant_live = collect().get(dominant) if traced_in_timed_region else None
+    dominant_live = p.collect().get(dominant) if traced_in_timed_region else None
     T.tamoe_trace_filter(None)
     T.tamoe_trace_clear()
 
-    # The other capacity mode beside the headline one (uniform <-> proportional to the target pattern):
-    # a short timed region of its own, same buffers; restored afterwards.
-    other_mode = None
-    if not args.graph:
-        K_main = int(off[-1].item())
-        _, _, cap_o = T.tamoe_topo_pattern(beta, level, wl.P, wl.N, wl.rank, wl.k, wl.S, wl.capacity_factor,
-                                           1 - args.cap_mode)
-        cap_keep = cap_d.clone()
-        cap_d.copy_(torch.from_numpy(cap_o).to(dev))
-        n_o = max(1, min(args.steps, 20))
-        for _ in range(2):
-            step()
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        for _ in range(n_o):
-            step()
-        torch.cuda.synchronize()
-        el_o = time.perf_counter() - t0
-        K_o = int(off[-1].item())
-        other_mode = {"cap_mode": 1 - args.cap_mode, "steps": n_o, "ms_per_step": round(el_o * 1e3 / n_o, 4),
-                      "value": round(S * n_o / el_o, 1), "unit": "tokens/s", "kept_rows_K": K_o,
-                      "drop_rate": round(1.0 - K_o / (S * k), 4)}
-        cap_d.copy_(cap_keep)
-        for _ in range(rotate):                  # slot, send and the size outputs are those of the headline mode again
-            step()
-        torch.cuda.synchronize()
-        assert int(off[-1].item()) == K_main
-
-    # Backward kernels (the next row of the scope after the forward path): measured in a pass of
-    # their own with events around every launch; they are not part of `value`.
-    backward = None
-    if not args.no_backward:
-        K_now = int(off[-1].item())
-        logits = torch.empty((S, N), dtype=f32, device=dev)
-        T.tamoe_gate(x, w, P, k, logits, topk_idx, topk_w, m, c_expert, c_device, ws, None)
-        dy = y                                   # any tensor of the shape of y serves as upstream gradient
-        d_recv = torch.empty((max(K_now, 1), d), dtype=x.dtype, device=dev)
-        d_w = torch.empty((S, k), dtype=f32, device=dev)
-        d_logits = torch.empty((S, N), dtype=f32, device=dev)
-        d_x = torch.empty((S, d), dtype=x.dtype, device=dev)
-
-        def bwd():
-            T.tamoe_combine_bwd(dy, send, K_now, slot, topk_w, d_recv, d_w, None)
-            T.tamoe_gate_bwd(logits, topk_idx, d_w, pen_d, c_expert, 1.0, P, d_logits, None)
-            T.tamoe_dispatch_bwd(d_recv, K_now, slot, d_x, None)
-
-        for _ in range(3):
-            bwd()
-        torch.cuda.synchronize()
-        reps = 10
-        T.tamoe_trace_start(3 * reps)
-        for _ in range(reps):
-            bwd()
-        torch.cuda.synchronize()
-        rec = collect()
-        T.tamoe_trace_clear()
-        live_b = int((slot >= 0).any(dim=1).sum().item())
-        rowb = d * b
-        bwd_bytes = {"combine_bwd_kernel": S * rowb + 2 * K_now * rowb + S * k * 12,
-                     "gate_bwd_kernel": 2 * S * N * 4 + S * k * 8,
-                     "dispatch_bwd_kernel": K_now * rowb + S * rowb + S * k * 4}
-        backward = []
-        for name, ts in rec.items():
-            us = float(np.mean(ts)) * 1e3
-            gbs = bwd_bytes[name] / (us * 1e-6) / 1e9
-            backward.append({"kernel": name, "avg_us": round(us, 2), "algo_bytes": int(bwd_bytes[name]),
-                             "achieved_GBs": round(gbs, 1), "frac_of_hbm_peak": round(gbs / HBM_PEAK_GBS, 4)})
-        del logits, d_recv, d_w, d_logits, d_x
-
-    # Receive-side regrouping (next row of the scope): the K_now rows of `send` stand in for a receive
-    # buffer with P source chunks x E local experts (E = 2 when the workload has one expert per device,
-    # where regrouping is the identity), seeded Poisson segment sizes.  Untimed pass, not part of `value`.
-    regroup = None
-    if not args.no_backward:
-        E_r = wl.E if wl.E > 1 else 2
-        P_r = min(wl.P, 128 // E_r)
-        rows_r = int(off[-1].item())
-        if rows_r >= P_r * E_r:
-            rng = np.random.Generator(np.random.Philox(key=[wl.seed, 11]))
-            share = rng.poisson(64, size=(P_r, E_r)).astype(np.float64) + 1.0
-            cnt = np.floor(share / share.sum() * rows_r).astype(np.int32)
-            cnt[0, 0] += rows_r - int(cnt.sum())
-            cnt_d = torch.from_numpy(cnt).to(dev)
-            rin = send[:rows_r]
-            rout = torch.empty_like(rin)
-            for _ in range(2):
-                T.tamoe_regroup(rin, cnt_d, True, rout, None, ws, None)
-            torch.cuda.synchronize()
-            T.tamoe_trace_filter("regroup_copy_kernel")
-            T.tamoe_trace_start(10)
-            for _ in range(10):
-                T.tamoe_regroup(rin, cnt_d, True, rout, None, ws, None)
-            torch.cuda.synchronize()
-            rec = collect()
-            T.tamoe_trace_filter(None)
-            T.tamoe_trace_clear()
-            us = float(np.mean(rec["regroup_copy_kernel"])) * 1e3
-            rb = 2 * rows_r * d * b
-            regroup = {"kernel": "regroup_copy_kernel", "P": P_r, "E": E_r, "rows": rows_r, "avg_us": round(us, 2),
-                       "algo_bytes": int(rb), "achieved_GBs": round(rb / (us * 1e-6) / 1e9, 1),
-                       "frac_of_hbm_peak": round(rb / (us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)}
-            del rout
-
-    # Variants (a further row of the scope): the fixed-size zero-padded layout against the packed one
-    # (bytes written and time of the row movers), and the weight renormalisation.  Untimed pass.
-    variants = None
-    if not args.no_backward:
-        C = int(cap_d.max().item())
-        pad_rows = N * C
-        send_p = torch.empty((pad_rows, d), dtype=x.dtype, device=dev)
-        slot_p = torch.empty_like(slot)
-        kept_p = torch.empty_like(kept)
-        w_n = torch.empty_like(topk_w)
-        d_wn = torch.empty_like(topk_w)
-
-        def var():
-            T.tamoe_dispatch_padded(x, topk_idx, cap_d, N, P, C, send_p, slot_p, kept_p, ws, None)
-            T.tamoe_renorm_topk(topk_w, w_n, None)
-            T.tamoe_renorm_topk_bwd(topk_w, w_n, d_wn, None)
-
-        for _ in range(2):
-            var()
-        torch.cuda.synchronize()
-        reps = 10
-        T.tamoe_trace_start(7 * reps)
-        for _ in range(reps):
-            var()
-        torch.cuda.synchronize()
-        rec = collect()
-        T.tamoe_trace_clear()
-        K_p = int(kept_p.sum().item())
-        live_p = int((slot_p >= 0).any(dim=1).sum().item())
-        us = {n: float(np.mean(ts)) * 1e3 for n, ts in rec.items()}
-        mover_us = us["dispatch_copy_kernel"] + us["dispatch_pad_fill_kernel"]
-        mover_bytes = (live_p + pad_rows) * d * b + S * k * 8
-        variants = {
-            "padded_dispatch": {"C": C, "rows_written": pad_rows, "rows_kept": K_p,
-                                "copy_us": round(us["dispatch_copy_kernel"], 2),
-                                "pad_fill_us": round(us["dispatch_pad_fill_kernel"], 2),
-                                "algo_bytes": int(mover_bytes),
-                                "achieved_GBs": round(mover_bytes / (mover_us * 1e-6) / 1e9, 1),
-                                "rows_vs_packed": round(pad_rows / max(K_p, 1), 4)},
-            "renorm_topk_us": round(us["renorm_topk_kernel"], 2),
-            "renorm_topk_bwd_us": round(us["renorm_topk_bwd_kernel"], 2),
-        }
-        del send_p, slot_p, kept_p, w_n, d_wn
+    other_mode = None if args.graph else measure_other_mode(p, args.cap_mode, args.steps)
+    extras = not args.no_extras
+    backward = measure_backward(p) if extras else None
+    regroup = measure_regroup(p) if extras else None
+    variants = measure_variants(p) if extras else None
 
     ms_per_step = elapsed * 1e3 / args.steps
     tokens_per_s = S * args.steps / elapsed
 
     # realised routing (for the algorithmic byte counts)
-    K = int(off[-1].item())
-    live_tokens = int((slot >= 0).any(dim=1).sum().item())
-    row = d * b
+    K = p.kept_rows()
+    live_tokens = p.live_tokens()
     algo_bytes = {
         "gate_bf16_kernel": S * row + N * row + S * k * 8,
         "gate_gemm_f32_kernel": S * row + N * row + S * N * 4,
@@ -433,18 +464,15 @@ def main():
     }
     kernels = []
     for name, ts in per_kernel.items():
-        avg_ms = float(np.mean(ts))
-        entry = {"kernel": name, "launches": len(ts), "avg_us": round(avg_ms * 1e3, 2)}
+        entry = {"kernel": name, "launches": len(ts), "avg_us": round(_mean_us(ts), 2)}
         if name in algo_bytes:
-            entry["algo_bytes"] = int(algo_bytes[name])
-            entry["achieved_GBs"] = round(algo_bytes[name] / (avg_ms * 1e-3) / 1e9, 1)
-            entry["frac_of_hbm_peak"] = round(entry["achieved_GBs"] / HBM_PEAK_GBS, 4)
+            entry.update(_rate(algo_bytes[name], _mean_us(ts)))
         kernels.append(entry)
     kernels.sort(key=lambda e: -e["avg_us"])
     roofline = None
     if dominant in algo_bytes:
         live = dominant_live if dominant_live else per_kernel[dominant]
-        dom_us = float(np.mean(live)) * 1e3
+        dom_us = _mean_us(live)
         gbs = algo_bytes[dominant] / (dom_us * 1e-6) / 1e9
         roofline = {"kernel": dominant, "bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS,
                     "unit": "GB/s", "frac": round(gbs / HBM_PEAK_GBS, 4),
@@ -468,23 +496,22 @@ def main():
         "vs_baseline": None,
         "dtype": "bf16" if wl.dtype == W.BF16 else "f32",
         "data": "synthetic",
-        "config": {"workload": wl.name, "S": S, "d": d, "N": N, "k": k, "P": P, "E": wl.E,
+        "config": {"workload": wl.name, "S": S, "d": wl.d, "N": N, "k": k, "P": wl.P, "E": wl.E,
                    "capacity_factor": wl.capacity_factor, "cap_mode": args.cap_mode,
                    "topology": f"{wl.nodes}x{wl.devs_per_node} ratio {wl.bw_ratio:g}:1", "rank": wl.rank,
                    "kept_rows_K": K, "tokens_with_a_kept_choice": live_tokens,
-                   "drop_rate": round(1.0 - K / (S * k), 4), "rotating_buffer_sets": rotate},
+                   "drop_rate": round(1.0 - K / (S * k), 4), "rotating_buffer_sets": p.rotate},
         "path_algo_bytes_per_step": int(total_algo),
         "path_achieved_GBs": round(total_algo / (ms_per_step * 1e-3) / 1e9, 1),
         "roofline": roofline,
-        "copy_probe": {"bytes_moved": int(2 * S * d * b), "median_us": round(copy_us, 2),
-                       "GBs": round(copy_gbs, 1), "frac_of_hbm_peak": round(copy_gbs / HBM_PEAK_GBS, 4)},
-        "mix_probe": mix,
+        "copy_probe": copy_probe,
+        "mix_probe": mix_probe,
         "kernels": kernels,
         "backward_kernels": backward,
         "regroup_kernel": regroup,
         "variants": variants,
         "other_capacity_mode": other_mode,
-        "l_topo": float(loss.item()),
+        "l_topo": float(p.loss.item()),
         "mode": "graph replay" if args.graph else "eager",
         "kernels_table_from": f"untimed pass of {table_steps} steps with HIP events around every launch",
     }
