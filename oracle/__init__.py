@@ -19,6 +19,7 @@ _SO = os.path.join(_HERE, "libtamoe_oracle.so")
 
 F32 = 0
 BF16 = 1
+F16 = 2
 
 _lib = None
 
@@ -45,6 +46,8 @@ def _load():
         "orc_set_threads": (None, [c_i32]),
         "orc_max_threads": (c_i32, []),
         "orc_round_to_bf16": (ctypes.c_uint16, [c_dbl]),
+        "orc_round_to_f16": (ctypes.c_uint16, [c_dbl]),
+        "orc_half_value": (c_dbl, [ctypes.c_uint16]),
         "orc_smooth_beta": (c_i32, [c_vp, c_vp, c_i32, c_vp]),
         "orc_target_pattern": (None, [c_vp, c_i32, c_i32, c_i32, c_i32, c_i64, c_vp]),
         "orc_penalty": (None, [c_vp, c_i32, c_vp]),
@@ -101,6 +104,16 @@ def set_threads(n: int) -> None:
 
 def max_threads() -> int:
     return int(_load().orc_max_threads())
+
+
+def round_to_f16(v: float) -> int:
+    """Bit pattern of the half-precision value nearest to the double v (ties to even)."""
+    return int(_load().orc_round_to_f16(float(v)))
+
+
+def half_value(bits: int) -> float:
+    """Exact value of a half-precision bit pattern."""
+    return float(_load().orc_half_value(int(bits)))
 
 
 def round_to_bf16(v: float) -> int:

@@ -38,6 +38,7 @@
 
 #define ORC_F32 0
 #define ORC_BF16 1
+#define ORC_F16 2
 
 static int g_threads = 1;
 
@@ -56,11 +57,57 @@ int orc_max_threads(void)
 
 static size_t elem_size(int dtype) { return dtype == ORC_F32 ? 4u : 2u; }
 
-/* exact value of element i of a float32 / bfloat16 buffer */
+/* exact value of an IEEE half-precision bit pattern (1 sign, 5 exponent, 10 fraction bits) */
+static double half_value(uint16_t h)
+{
+    int sign = h >> 15, ex = (h >> 10) & 31, frac = h & 1023;
+    double v;
+    if (ex == 31)
+        v = frac ? NAN : INFINITY;
+    else if (ex == 0)
+        v = ldexp((double)frac, -24);               /* subnormal: frac * 2^-24 */
+    else
+        v = ldexp(1.0 + (double)frac / 1024.0, ex - 15);
+    return sign ? -v : v;
+}
+
+/* nearest half-precision value (11 significand bits), ties to even, straight from double */
+static uint16_t round_to_f16(double v)
+{
+    uint16_t sign = (uint16_t)(signbit(v) ? 0x8000u : 0u);
+    if (isnan(v))
+        return (uint16_t)0x7E00u;
+    double a = fabs(v);
+    if (a == 0.0)
+        return sign;
+    if (isinf(v))
+        return (uint16_t)(sign | 0x7C00u);
+    int ex;
+    (void)frexp(a, &ex);
+    int e = ex - 1;                 /* floor(log2 a) */
+    if (e < -14)
+        e = -14;                    /* subnormal range shares the spacing of the smallest normal */
+    double ulp = ldexp(1.0, e - 10);
+    double q = nearbyint(a / ulp);  /* to nearest, ties to even; q <= 2048 */
+    double r = q * ulp;
+    if (r >= 65520.0)               /* halfway between the largest finite value and 2^16 rounds to infinity */
+        return (uint16_t)(sign | 0x7C00u);
+    if (r < ldexp(1.0, -14))        /* subnormal (or zero): the fraction field is r / 2^-24 */
+        return (uint16_t)(sign | (uint16_t)(r / ldexp(1.0, -24)));
+    int re;
+    double f = frexp(r, &re);       /* r = f * 2^re, f in [0.5, 1) */
+    int biased = re - 1 + 15;
+    int frac = (int)((f * 2.0 - 1.0) * 1024.0);
+    return (uint16_t)(sign | (uint16_t)(biased << 10) | (uint16_t)frac);
+}
+
+/* exact value of element i of a float32 / bfloat16 / half-precision buffer */
 static double load_elem(const void *buf, int dtype, int64_t i)
 {
     if (dtype == ORC_F32)
         return (double)((const float *)buf)[i];
+    if (dtype == ORC_F16)
+        return half_value(((const uint16_t *)buf)[i]);
     uint32_t bits = (uint32_t)((const uint16_t *)buf)[i] << 16;
     float f;
     memcpy(&f, &bits, 4);
@@ -97,12 +144,16 @@ static void store_elem(void *buf, int dtype, int64_t i, double v)
 {
     if (dtype == ORC_F32)
         ((float *)buf)[i] = (float)v;
+    else if (dtype == ORC_F16)
+        ((uint16_t *)buf)[i] = round_to_f16(v);
     else
         ((uint16_t *)buf)[i] = round_to_bf16(v);
 }
 
-/* exported so the rounding itself can be pinned by a test */
+/* exported so the roundings and the half-precision decoding can be pinned by tests */
 uint16_t orc_round_to_bf16(double v) { return round_to_bf16(v); }
+uint16_t orc_round_to_f16(double v) { return round_to_f16(v); }
+double orc_half_value(uint16_t h) { return half_value(h); }
 
 /* ---- setup: communication model, target pattern, penalty ----------------- */
 

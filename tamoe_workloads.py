@@ -22,6 +22,7 @@ import numpy as np
 
 F32 = 0
 BF16 = 1
+F16 = 2      # IEEE half precision, the data type of the paper's cluster-A runs (GPT model table)
 
 
 @dataclass(frozen=True)
@@ -31,7 +32,7 @@ class Workload:
     name: str
     S: int            # tokens on this device
     d: int            # hidden size
-    dtype: int        # F32 or BF16 storage of x, W and y
+    dtype: int        # F32, BF16 or F16 storage of x, W and y
     N: int            # experts
     k: int            # experts selected per token
     capacity_factor: float
@@ -92,9 +93,12 @@ def bf16_bits_to_f32(b: np.ndarray) -> np.ndarray:
 
 
 def to_storage(a: np.ndarray, dtype: int) -> np.ndarray:
-    """float32 array -> the array that is handed to both sides (float32, or uint16 bf16 bits)."""
+    """float32 array -> the array that is handed to both sides (float32, or uint16 bit patterns of
+    bfloat16 / half precision values)."""
     if dtype == F32:
         return np.ascontiguousarray(a, dtype=np.float32)
+    if dtype == F16:
+        return np.ascontiguousarray(a, dtype=np.float32).astype(np.float16).view(np.uint16)
     return f32_to_bf16_bits(a)
 
 
@@ -102,6 +106,8 @@ def storage_to_f64(a: np.ndarray, dtype: int) -> np.ndarray:
     """Exact values of a storage buffer as float64 (for test-side inspection only)."""
     if dtype == F32:
         return a.astype(np.float64)
+    if dtype == F16:
+        return np.ascontiguousarray(a, dtype=np.uint16).view(np.float16).astype(np.float64)
     return bf16_bits_to_f32(a).astype(np.float64)
 
 
