@@ -39,6 +39,8 @@ def parse_args():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="large")
+    ap.add_argument("--dtype", choices=["f32", "bf16", "f16"], default=None,
+                    help="storage type instead of the workload's own (f16: the FP16 of the paper's GPT model table)")
     ap.add_argument("--cap-mode", type=int, default=0, help="0 uniform capacity, 1 proportional to the target pattern")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", "--no-backward", dest="no_extras", action="store_true",
@@ -173,6 +175,8 @@ class Path:
         t = self.torch.from_numpy(a)
         if self.wl.dtype == self.W.BF16:
             t = t.view(self.torch.int16).view(self.torch.bfloat16)
+        elif self.wl.dtype == self.W.F16:
+            t = t.view(self.torch.int16).view(self.torch.float16)
         return t.to(self.dev)
 
     def step(self):
@@ -395,6 +399,10 @@ def main():
         sys.exit(2)
     T.lib()
     wl = W.WORKLOADS[args.workload]
+    if args.dtype is not None:
+        import dataclasses
+
+        wl = dataclasses.replace(wl, dtype={"f32": W.F32, "bf16": W.BF16, "f16": W.F16}[args.dtype])
     p = Path(T, W, torch, wl, args.cap_mode, max(1, args.rotate))
     S, N, k, row = wl.S, wl.N, wl.k, p.row_bytes
 
@@ -457,6 +465,7 @@ def main():
     live_tokens = p.live_tokens()
     algo_bytes = {
         "gate_bf16_kernel": S * row + N * row + S * k * 8,
+        "gate_f16_kernel": S * row + N * row + S * k * 8,
         "gate_gemm_f32_kernel": S * row + N * row + S * N * 4,
         "select_kernel": S * N * 4 + S * k * 8,
         "dispatch_copy_kernel": live_tokens * row + K * row + S * k * 8,
@@ -481,7 +490,7 @@ def main():
                     "launches_timed": len(live),
                     "timed_in": "timed region" if dominant_live else "table pass"}
 
-    total_algo = algo_bytes["gate_bf16_kernel" if wl.dtype == W.BF16 else "gate_gemm_f32_kernel"] \
+    total_algo = algo_bytes["gate_gemm_f32_kernel" if wl.dtype == W.F32 else "gate_bf16_kernel"] \
         + algo_bytes["dispatch_copy_kernel"] + algo_bytes["combine_kernel"]
     result = {
         "metric": "routed tokens/sec (gate+aux_loss+dispatch+combine), 1 GPU",
@@ -494,7 +503,7 @@ def main():
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "bf16" if wl.dtype == W.BF16 else "f32",
+        "dtype": {W.F32: "f32", W.BF16: "bf16", W.F16: "f16"}[wl.dtype],
         "data": "synthetic",
         "config": {"workload": wl.name, "S": S, "d": wl.d, "N": N, "k": k, "P": wl.P, "E": wl.E,
                    "capacity_factor": wl.capacity_factor, "cap_mode": args.cap_mode,

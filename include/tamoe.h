@@ -35,8 +35,9 @@
  *  - Device functions only enqueue work on `stream` (a hipStream_t passed as void*; NULL is
  *    the default stream).  They never synchronise and are deterministic: same inputs, same
  *    bits.
- *  - dtype: TAMOE_F32 (float) or TAMOE_BF16 (bfloat16 bit patterns, 2 bytes per element).
- *    A token row must be a multiple of 16 bytes (d % 4 == 0 for F32, d % 8 == 0 for BF16) and
+ *  - dtype: TAMOE_F32 (float), TAMOE_BF16 (bfloat16) or TAMOE_F16 (IEEE half precision, the FP16 of
+ *    the paper's GPT model table); the 2-byte types are passed as bit patterns.
+ *    A token row must be a multiple of 16 bytes (d % 4 == 0 for F32, d % 8 == 0 otherwise) and
  *    x, W, send, recv, y must be 16-byte aligned.
  *  - Limits: 1 <= N <= TAMOE_MAX_EXPERTS, 1 <= k <= min(N, TAMOE_MAX_K), N % P == 0,
  *    S * k < 2^31.  S = 0 is accepted by every device function except tamoe_aux_loss.
@@ -68,7 +69,7 @@ typedef enum tamoe_status {
     TAMOE_HIP_ERROR = 4           /* a kernel launch was rejected by the HIP runtime */
 } tamoe_status;
 
-enum { TAMOE_F32 = 0, TAMOE_BF16 = 1 };
+enum { TAMOE_F32 = 0, TAMOE_BF16 = 1, TAMOE_F16 = 2 };
 enum { TAMOE_CAP_UNIFORM = 0, TAMOE_CAP_PROPORTIONAL = 1 };
 enum { TAMOE_NORM_L1 = 0, TAMOE_NORM_SOFTMAX = 1 };
 

@@ -22,6 +22,7 @@ LIB_PATH = os.path.join(_HERE, "libtamoe.so")
 
 F32 = 0
 BF16 = 1
+F16 = 2
 CAP_UNIFORM = 0
 CAP_PROPORTIONAL = 1
 NORM_L1 = 0
@@ -129,7 +130,9 @@ def _dtype_code(t: torch.Tensor) -> int:
         return F32
     if t.dtype == torch.bfloat16:
         return BF16
-    raise TamoeError(UNSUPPORTED, f"storage dtype {t.dtype} is neither float32 nor bfloat16")
+    if t.dtype == torch.float16:
+        return F16
+    raise TamoeError(UNSUPPORTED, f"storage dtype {t.dtype} is none of float32, bfloat16, float16")
 
 
 def _dev(t: Optional[torch.Tensor], dtype: Optional[torch.dtype], name: str):

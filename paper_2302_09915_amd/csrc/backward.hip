@@ -325,6 +325,8 @@ extern "C" int tamoe_combine_bwd(const void* dy, const void* recv, int64_t K_row
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (dtype == TAMOE_F32)
         launch_combine_bwd<TAMOE_F32>(dy, recv, K_rows, slot, topk_w, S, k, cpr, d_recv, d_topk_w, st);
+    else if (dtype == TAMOE_F16)
+        launch_combine_bwd<TAMOE_F16>(dy, recv, K_rows, slot, topk_w, S, k, cpr, d_recv, d_topk_w, st);
     else
         launch_combine_bwd<TAMOE_BF16>(dy, recv, K_rows, slot, topk_w, S, k, cpr, d_recv, d_topk_w, st);
     return check_launch(fn, "combine_bwd_kernel");

@@ -119,6 +119,8 @@ static int combine_entry(const char* fn, const void* recv, int64_t K_rows, const
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (dtype == TAMOE_F32)
         launch_combine<TAMOE_F32>(recv, K_rows, slot, weighted ? topk_w : nullptr, S, k, cpr, y, st);
+    else if (dtype == TAMOE_F16)
+        launch_combine<TAMOE_F16>(recv, K_rows, slot, weighted ? topk_w : nullptr, S, k, cpr, y, st);
     else
         launch_combine<TAMOE_BF16>(recv, K_rows, slot, weighted ? topk_w : nullptr, S, k, cpr, y, st);
     return check_launch(fn, "combine_kernel");

@@ -24,6 +24,7 @@
 namespace tamoe {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 constexpr int kKC = 64;                 // K elements per chunk (128 bytes of a bf16 row)
@@ -271,9 +272,9 @@ __device__ __forceinline__ void store_block_partials(const float (*m_w)[NB * 32]
 }
 
 // KTAIL: d is not a multiple of the 64-element K chunk (the last chunk is partly out of range).
-template <int NB, int WAVES, bool KTAIL>
-__global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu((NB == 4 && WAVES < 4) ? 1 : 2)))
-void gate_bf16_kernel(
+// F16: the 2-byte elements are IEEE half precision instead of bfloat16; only the MFMA differs.
+template <int NB, int WAVES, bool KTAIL, bool F16>
+__device__ __forceinline__ void gate_mfma_tile(
     const uint16_t* __restrict__ x, const uint16_t* __restrict__ w, int64_t S, int d, int N, int k,
     float* __restrict__ logits, int32_t* __restrict__ topk_idx, float* __restrict__ topk_w,
     float* __restrict__ m_part, int32_t* __restrict__ c_part, int n_blocks) {
@@ -392,11 +393,16 @@ void gate_bf16_kernel(
         const unsigned char* xl = &x_lds[buf][(wave * 32 + r) * kLdsRow + half * 64];
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const bf16x8 b = *reinterpret_cast<const bf16x8*>(xl + i * 16);
+            const vec16 b = *reinterpret_cast<const vec16*>(xl + i * 16);
 #pragma unroll
             for (int nb = 0; nb < NB; ++nb) {
-                const bf16x8 a = *reinterpret_cast<const bf16x8*>(wl + nb * 32 * kLdsRow + i * 16);
-                acc[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[nb], 0, 0, 0);
+                const vec16 a = *reinterpret_cast<const vec16*>(wl + nb * 32 * kLdsRow + i * 16);
+                if constexpr (F16)
+                    acc[nb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a),
+                                                                      __builtin_bit_cast(f16x8, b), acc[nb], 0, 0, 0);
+                else
+                    acc[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a),
+                                                                       __builtin_bit_cast(bf16x8, b), acc[nb], 0, 0, 0);
             }
         }
     };
@@ -452,6 +458,24 @@ void gate_bf16_kernel(
     select_tile<NB>(sc, lane, token, token_ok, N, k, logits, topk_idx, topk_w, m_w[wave], hist, tile, S);
     store_block_partials<NB, WAVES>(m_w, hist, N, n_blocks, m_part, c_part);
 }
+
+#define TAMOE_GATE_ARGS                                                                                     \
+    const uint16_t *__restrict__ x, const uint16_t *__restrict__ w, int64_t S, int d, int N, int k,         \
+        float *__restrict__ logits, int32_t *__restrict__ topk_idx, float *__restrict__ topk_w,             \
+        float *__restrict__ m_part, int32_t *__restrict__ c_part, int n_blocks
+
+template <int NB, int WAVES, bool KTAIL>
+__global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu((NB == 4 && WAVES < 4) ? 1 : 2)))
+void gate_bf16_kernel(TAMOE_GATE_ARGS) {
+    gate_mfma_tile<NB, WAVES, KTAIL, false>(x, w, S, d, N, k, logits, topk_idx, topk_w, m_part, c_part, n_blocks);
+}
+
+template <int NB, int WAVES, bool KTAIL>
+__global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu((NB == 4 && WAVES < 4) ? 1 : 2)))
+void gate_f16_kernel(TAMOE_GATE_ARGS) {
+    gate_mfma_tile<NB, WAVES, KTAIL, true>(x, w, S, d, N, k, logits, topk_idx, topk_w, m_part, c_part, n_blocks);
+}
+#undef TAMOE_GATE_ARGS
 
 // fp32 scores: 64 tokens x N experts per workgroup, K in chunks of 32 through LDS, one fp32 FMA
 // per term in ascending K.
@@ -570,16 +594,22 @@ __global__ __launch_bounds__(256) void gate_finalize_kernel(const float* __restr
 
 // ---- host side ------------------------------------------------------------------------------
 
-template <int NB>
-static void launch_gate_bf16(int waves, int64_t blocks, hipStream_t st, const uint16_t* x, const uint16_t* w,
+template <int NB, bool F16>
+static void launch_gate_mfma(int waves, int64_t blocks, hipStream_t st, const uint16_t* x, const uint16_t* w,
                              int64_t S, int d, int N, int k, float* logits, int32_t* topk_idx, float* topk_w,
                              float* m_part, int32_t* c_part) {
     const dim3 grid((unsigned)blocks);
     const bool ktail = d % kKC != 0;
-    TraceScope tr("gate_bf16_kernel", st);
-#define TAMOE_GATE_LAUNCH(WV, KT)                                                                                 \
-    gate_bf16_kernel<NB, WV, KT><<<grid, dim3(WV * 64), 0, st>>>(x, w, S, d, N, k, logits, topk_idx, topk_w, m_part, \
-                                                                  c_part, (int)blocks)
+    TraceScope tr(F16 ? "gate_f16_kernel" : "gate_bf16_kernel", st);
+#define TAMOE_GATE_LAUNCH(WV, KT)                                                                                  \
+    do {                                                                                                           \
+        if constexpr (F16)                                                                                         \
+            gate_f16_kernel<NB, WV, KT><<<grid, dim3(WV * 64), 0, st>>>(x, w, S, d, N, k, logits, topk_idx, topk_w, \
+                                                                         m_part, c_part, (int)blocks);              \
+        else                                                                                                       \
+            gate_bf16_kernel<NB, WV, KT><<<grid, dim3(WV * 64), 0, st>>>(x, w, S, d, N, k, logits, topk_idx,       \
+                                                                          topk_w, m_part, c_part, (int)blocks);     \
+    } while (0)
     if (waves == 8) {
         if constexpr (NB >= 2) {
             if (ktail) TAMOE_GATE_LAUNCH(8, true); else TAMOE_GATE_LAUNCH(8, false);
@@ -672,19 +702,29 @@ extern "C" int tamoe_gate(const void* x, const void* w, int dtype, int64_t S, in
     float* m_part = reinterpret_cast<float*>(static_cast<char*>(ws) + lay.m_part);
     int32_t* c_part = reinterpret_cast<int32_t*>(static_cast<char*>(ws) + lay.c_part);
     int64_t blocks = 0;
-    if (S > 0 && dtype == TAMOE_BF16) {
+    if (S > 0 && dtype != TAMOE_F32) {
         const int waves = gate_waves(S, N);
         blocks = ceil_div(S, 32 * (int64_t)waves);
         if (blocks > 0x7fffffff) return fail(TAMOE_UNSUPPORTED, "%s: too many token tiles", fn);
         const uint16_t* xb = static_cast<const uint16_t*>(x);
         const uint16_t* wb = static_cast<const uint16_t*>(w);
+#define TAMOE_GATE_NB(NBV)                                                                                          \
+    do {                                                                                                            \
+        if (dtype == TAMOE_F16)                                                                                     \
+            launch_gate_mfma<NBV, true>(waves, blocks, st, xb, wb, S, d, N, k, logits, topk_idx, topk_w, m_part,    \
+                                        c_part);                                                                    \
+        else                                                                                                        \
+            launch_gate_mfma<NBV, false>(waves, blocks, st, xb, wb, S, d, N, k, logits, topk_idx, topk_w, m_part,   \
+                                         c_part);                                                                   \
+    } while (0)
         if (N <= 32)
-            launch_gate_bf16<1>(waves, blocks, st, xb, wb, S, d, N, k, logits, topk_idx, topk_w, m_part, c_part);
+            TAMOE_GATE_NB(1);
         else if (N <= 64)
-            launch_gate_bf16<2>(waves, blocks, st, xb, wb, S, d, N, k, logits, topk_idx, topk_w, m_part, c_part);
+            TAMOE_GATE_NB(2);
         else
-            launch_gate_bf16<4>(waves, blocks, st, xb, wb, S, d, N, k, logits, topk_idx, topk_w, m_part, c_part);
-        if ((rc = check_launch(fn, "gate_bf16_kernel")) != TAMOE_OK) return rc;
+            TAMOE_GATE_NB(4);
+#undef TAMOE_GATE_NB
+        if ((rc = check_launch(fn, dtype == TAMOE_F16 ? "gate_f16_kernel" : "gate_bf16_kernel")) != TAMOE_OK) return rc;
     } else if (S > 0) {
         float* lg = logits != nullptr ? logits : reinterpret_cast<float*>(static_cast<char*>(ws) + lay.logits);
         const dim3 grid((unsigned)ceil_div(S, 64)), block(256);

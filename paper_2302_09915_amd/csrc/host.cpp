@@ -63,8 +63,8 @@ int check_shape(const char* fn, int64_t S, int N, int P, int k) {
 }
 
 int check_rows(const char* fn, int dtype, int d) {
-    if (dtype != TAMOE_F32 && dtype != TAMOE_BF16)
-        return fail(TAMOE_UNSUPPORTED, "%s: dtype %d is neither TAMOE_F32 nor TAMOE_BF16", fn, dtype);
+    if (dtype != TAMOE_F32 && dtype != TAMOE_BF16 && dtype != TAMOE_F16)
+        return fail(TAMOE_UNSUPPORTED, "%s: dtype %d is none of TAMOE_F32, TAMOE_BF16, TAMOE_F16", fn, dtype);
     if (d <= 0) return fail(TAMOE_INVALID_ARG, "%s: d = %d must be positive", fn, d);
     if (((int64_t)d * elem_bytes(dtype)) % 16 != 0)
         return fail(TAMOE_UNSUPPORTED, "%s: a row of d = %d elements is not a multiple of 16 bytes", fn, d);

@@ -41,25 +41,39 @@ def to_dev(a: np.ndarray, dtype: int):
     t = torch.from_numpy(a)
     if dtype == W.BF16:
         t = t.view(torch.int16).view(torch.bfloat16)
+    elif dtype == W.F16:
+        t = t.view(torch.int16).view(torch.float16)
     return t.cuda()
 
 
 def to_host(t, dtype: int) -> np.ndarray:
-    if dtype == W.BF16:
+    if dtype in (W.BF16, W.F16):
         return t.view(torch.int16).cpu().numpy().view(np.uint16)
     return t.cpu().numpy()
 
 
+def torch_dtype(dtype: int):
+    return {W.F32: torch.float32, W.BF16: torch.bfloat16, W.F16: torch.float16}[dtype]
+
+
 def ulp_of(v: np.ndarray, dtype: int) -> np.ndarray:
-    """Spacing of the storage type at |v| (float64 in, float64 out)."""
-    mant = 7 if dtype == W.BF16 else 23
+    """Spacing of the storage type at |v| (float64 in, float64 out); below the smallest normal value
+    the spacing is that of the subnormals."""
+    mant, e_min = {W.F32: (23, -126), W.BF16: (7, -126), W.F16: (10, -14)}[dtype]
     a = np.abs(v)
-    e = np.floor(np.log2(np.maximum(a, 2.0 ** -126)))
+    e = np.floor(np.log2(np.maximum(a, 2.0 ** e_min)))
     return 2.0 ** (e - mant)
 
 
+def flip_bound(dtype: int, k: int) -> float:
+    """Share of elements that may differ by one storage ulp from the oracle's once-rounded value: the
+    fp32 accumulation error (about (k+1) roundings of 2^-24) lets a sum cross a rounding boundary of
+    the storage type with probability ~ 2 * error / ulp; bfloat16: ulp 2^-8 relative, half: 2^-11."""
+    return 1e-3 if dtype == W.BF16 else max(1e-3, 4.0 * (k + 1) * 2.0 ** -24 / 2.0 ** -11)
+
+
 def check_logits(gpu: np.ndarray, ref: np.ndarray, dtype: int):
-    tol = 1e-3 if dtype == W.BF16 else 1e-5
+    tol = 1e-3 if dtype != W.F32 else 1e-5
     diff = np.abs(gpu.astype(np.float64) - ref)
     assert diff.max() <= tol * np.abs(ref).max()
     rms = math.sqrt(float((ref ** 2).mean()))
@@ -88,12 +102,12 @@ def check_combine(y_gpu: np.ndarray, y_exact: np.ndarray, y_ref: np.ndarray, mag
     arith = 4.0 * k * 2.0 ** -24 * mag
     bound = 0.5 * ulp_of(y_exact, dtype) + arith + 2.0 ** -149
     assert (np.abs(yv - y_exact) <= bound).all()
-    if dtype == W.BF16:
+    if dtype != W.F32:
         # the storage ulp dwarfs the fp32 accumulation error: the once-rounded results agree except
         # where the exact sum sits on a rounding boundary
         flips = (y_gpu != y_ref)
         flips &= ~((W.storage_to_f64(y_ref, dtype) == 0) & (yv == 0))      # +0 / -0 are the same value
-        assert flips.mean() <= 1e-3
+        assert flips.mean() <= flip_bound(dtype, k)
     else:
         assert (np.abs(yv - y_exact) <= 1e-5 * np.maximum(np.abs(y_exact), mag)).all()
 
@@ -168,7 +182,7 @@ def full_parity(T, oracle, spec, x_np, w_np, penalty, cap, sample=None):
     # E: end to end, oracle on its own scores (needs all tokens' scores: only when not sampled)
     if sample is None and S > 0:
         own = oracle.route_from_logits(ref_lg, k, P, penalty, cap)
-        tol = 1e-3 if dt == W.BF16 else 1e-5
+        tol = 1e-3 if dt != W.F32 else 1e-5
         assert g["l_topo"] == pytest.approx(own["l_topo"], rel=tol)
         assert g["l_aux"] == pytest.approx(own["l_aux"], rel=tol)
     return g, ref
@@ -197,6 +211,21 @@ def test_config_parity(T, oracle, name, cap_mode):
         assert share[0] > 0.2 and share[0] > 5 * share[16]
 
 
+@pytest.mark.parametrize("name", ["small", "gpt_moe", "skewed"])
+def test_config_parity_half_precision(T, oracle, name):
+    """The same configurations with half-precision storage, the data type of the paper's own runs on its
+    first cluster (GPT model table); inputs drawn as for bf16 and rounded to half precision."""
+    import dataclasses
+
+    wl = dataclasses.replace(W.WORKLOADS[name], dtype=W.F16)
+    oracle.set_threads(oracle.max_threads())
+    inp = W.make_inputs(wl)
+    assert inp["x"].dtype == np.uint16
+    beta, level = W.topology(wl)
+    c_hat, pen, cap = T.tamoe_topo_pattern(beta, level, wl.P, wl.N, 0, wl.k, wl.S, wl.capacity_factor, 0)
+    g, ref = full_parity(T, oracle, spec_of(wl), inp["x"], inp["w"], pen.astype(np.float64), cap)
+
+
 def test_large_config_parity_sampled(T, oracle):
     """Full size, the launch configuration the benchmark times.  Scores and combine are checked
     on a sample of tokens; selection, slots and the send buffer on every token."""
@@ -221,6 +250,10 @@ def test_large_config_parity_sampled(T, oracle):
     (W.BF16, 1000, 64, 128, 64, 8, 1.0),   # k at the limit, N at the limit
     (W.BF16, 2500, 264, 96, 8, 2, 2.0),    # several count tiles, ragged end
     (W.BF16, 70000, 16, 32, 4, 1, 1.1),    # many tokens, tiny rows
+    (W.F16, 33, 72, 5, 5, 2, 1.0),         # half precision: ragged tile, K tail, odd N
+    (W.F16, 2500, 264, 96, 8, 2, 2.0),
+    (W.F16, 1000, 64, 128, 64, 8, 1.0),
+    (W.F16, 40000, 128, 64, 8, 1, 1.0),    # four-wavefront workgroups
     (W.F32, 1, 4, 2, 1, 2, 1.0),
     (W.F32, 77, 36, 33, 11, 4, 0.7),
     (W.F32, 1500, 100, 128, 2, 2, 1.0),
@@ -240,13 +273,13 @@ def test_odd_shapes(T, oracle, dtype, S, d, N, P, k, cf):
 def _random_shape(i):
     """Seeded random shape inside the library's limits: ragged S, d any multiple of 16 bytes, any N % P == 0."""
     rng = np.random.default_rng(1000 + i)
-    dtype = W.BF16 if i % 4 else W.F32
+    dtype = (W.F32, W.BF16, W.F16, W.BF16)[i % 4]
     P = int(rng.choice([1, 2, 3, 4, 6, 8, 16, 32, 64]))
     E = int(rng.integers(1, max(2, 128 // P + 1)))
     N = P * E
     k = int(rng.integers(1, min(N, 8) + 1))
     S = int(rng.choice([rng.integers(1, 300), rng.integers(300, 5000), rng.integers(5000, 40000)]))
-    unit = 8 if dtype == W.BF16 else 4
+    unit = 4 if dtype == W.F32 else 8
     d = unit * int(rng.choice([rng.integers(1, 9), rng.integers(9, 80), rng.integers(80, 300)]))
     if S * d > 6_000_000:                                   # keep the oracle's fp64 score product to seconds
         S = max(1, 6_000_000 // d)

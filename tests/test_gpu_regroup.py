@@ -23,7 +23,7 @@ def T():
 
 @pytest.mark.parametrize("P,E,d,dtype,mean_rows", [
     (64, 2, 4096, W.BF16, 40), (8, 1, 64, W.F32, 100), (16, 8, 264, W.BF16, 9), (1, 5, 8, W.BF16, 3),
-    (3, 7, 100, W.F32, 30), (128, 1, 1024, W.BF16, 11), (4, 32, 16, W.BF16, 50)])
+    (3, 7, 100, W.F32, 30), (128, 1, 1024, W.BF16, 11), (4, 32, 16, W.BF16, 50), (8, 4, 520, W.F16, 25)])
 def test_regroup_matches_oracle_and_inverts(T, oracle, P, E, d, dtype, mean_rows):
     rng = np.random.default_rng(P * 131 + E)
     cnt = rng.poisson(mean_rows, size=(P, E)).astype(np.int32)

@@ -91,6 +91,7 @@ def _padded_case(T, oracle, S, d, N, P, k, C, dtype, cap, seed, skew=0.0):
     (512, 64, 8, 8, 1, 64, W.F32, False),            # Tiny-shaped
     (2048, 1024, 64, 64, 2, 77, W.BF16, True),
     (100, 8, 4, 2, 2, 1000, W.F32, True),            # C far above the load: mostly padding
+    (1500, 776, 32, 8, 2, 90, W.F16, True),          # half precision
 ])
 def test_dispatch_padded_matches_oracle(T, oracle, S, d, N, P, k, C, dtype, with_cap):
     cap = None
