@@ -38,7 +38,9 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="large")
+    ap.add_argument("--workload", default="large",
+                    help="tiny, small, gpt_moe, skewed, large (the measured configurations) or one of the paper's own "
+                         "shapes: paper_switch_fp16, paper_gshard_fp16, paper_switch_fp32, paper_gshard_fp32")
     ap.add_argument("--dtype", choices=["f32", "bf16", "f16"], default=None,
                     help="storage type instead of the workload's own (f16: the FP16 of the paper's GPT model table)")
     ap.add_argument("--cap-mode", type=int, default=0, help="0 uniform capacity, 1 proportional to the target pattern")
@@ -398,7 +400,7 @@ def main():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(2)
     T.lib()
-    wl = W.WORKLOADS[args.workload]
+    wl = W.workload(args.workload)
     if args.dtype is not None:
         import dataclasses
 

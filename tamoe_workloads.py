@@ -72,6 +72,32 @@ WORKLOADS: Dict[str, Workload] = {
 }
 
 
+# The shapes of the paper's own runs (Evaluation, GPT model table: hidden size 1024, Switch top-1 with
+# capacity factor 1.0 and GShard top-2 with 2.0 in FP16 on its first cluster, both gates with 1.2 in
+# FP32 on the other two; batch size 6 resp. 4 sequences per device, taken at 1024 tokens each; up to 64
+# experts, one per device, 8 devices per node).  Not among the five measured configurations: extra
+# shapes for the benchmark and one parity test each.  The bandwidth ratio is the GPT-MoE config's.
+PAPER_SHAPES: Dict[str, Workload] = {
+    "paper_switch_fp16": Workload("paper_switch_fp16", S=6144, d=1024, dtype=F16, N=64, k=1, capacity_factor=1.0,
+                                  nodes=8, devs_per_node=8, bw_ratio=10.0, seed=11),
+    "paper_gshard_fp16": Workload("paper_gshard_fp16", S=6144, d=1024, dtype=F16, N=64, k=2, capacity_factor=2.0,
+                                  nodes=8, devs_per_node=8, bw_ratio=10.0, seed=12),
+    "paper_switch_fp32": Workload("paper_switch_fp32", S=4096, d=1024, dtype=F32, N=64, k=1, capacity_factor=1.2,
+                                  nodes=8, devs_per_node=8, bw_ratio=10.0, seed=13),
+    "paper_gshard_fp32": Workload("paper_gshard_fp32", S=4096, d=1024, dtype=F32, N=64, k=2, capacity_factor=1.2,
+                                  nodes=8, devs_per_node=8, bw_ratio=10.0, seed=14),
+}
+
+
+def workload(name: str) -> Workload:
+    """A measured configuration or one of the paper's own shapes, by name."""
+    if name in WORKLOADS:
+        return WORKLOADS[name]
+    if name in PAPER_SHAPES:
+        return PAPER_SHAPES[name]
+    raise KeyError(f"unknown workload {name!r}; known: {sorted(WORKLOADS) + sorted(PAPER_SHAPES)}")
+
+
 # ----------------------------------------------------------------------------
 # storage-type helpers (bit manipulation only)
 # ----------------------------------------------------------------------------

@@ -226,6 +226,17 @@ def test_config_parity_half_precision(T, oracle, name):
     g, ref = full_parity(T, oracle, spec_of(wl), inp["x"], inp["w"], pen.astype(np.float64), cap)
 
 
+@pytest.mark.parametrize("name", sorted(W.PAPER_SHAPES))
+def test_paper_shapes_parity(T, oracle, name):
+    """The shapes of the paper's own runs (GPT model table): both gates, FP16 and FP32 storage."""
+    wl = W.PAPER_SHAPES[name]
+    oracle.set_threads(oracle.max_threads())
+    inp = W.make_inputs(wl)
+    beta, level = W.topology(wl)
+    c_hat, pen, cap = T.tamoe_topo_pattern(beta, level, wl.P, wl.N, wl.P // 2 + 1, wl.k, wl.S, wl.capacity_factor, 0)
+    full_parity(T, oracle, spec_of(wl), inp["x"], inp["w"], pen.astype(np.float64), cap)
+
+
 def test_large_config_parity_sampled(T, oracle):
     """Full size, the launch configuration the benchmark times.  Scores and combine are checked
     on a sample of tokens; selection, slots and the send buffer on every token."""

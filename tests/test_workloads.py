@@ -70,3 +70,17 @@ def test_random_routing_has_distinct_experts():
     assert all(len(set(r)) == 4 for r in idx) and idx.min() >= 0 and idx.max() < 16
     c = np.bincount(idx.ravel(), minlength=16)
     assert c[0] > c[15]
+
+
+def test_paper_shapes_are_the_gpt_model_table():
+    assert set(W.PAPER_SHAPES) == {"paper_switch_fp16", "paper_gshard_fp16", "paper_switch_fp32", "paper_gshard_fp32"}
+    for name, wl in W.PAPER_SHAPES.items():
+        assert wl.d == 1024 and wl.N == 64 and wl.P == 64 and wl.E == 1
+        assert wl.k == (1 if "switch" in name else 2)
+        assert wl.dtype == (W.F16 if "fp16" in name else W.F32)
+        assert W.workload(name) is wl
+    assert W.PAPER_SHAPES["paper_switch_fp16"].capacity_factor == 1.0
+    assert W.PAPER_SHAPES["paper_gshard_fp16"].capacity_factor == 2.0
+    assert W.workload("large") is W.WORKLOADS["large"]
+    x = W.make_inputs(W.PAPER_SHAPES["paper_gshard_fp16"], S=64)["x"]
+    assert x.dtype == np.uint16 and np.isfinite(W.storage_to_f64(x, W.F16)).all()
