@@ -468,7 +468,7 @@ def main():
     algo_bytes = {
         "gate_bf16_kernel": S * row + N * row + S * k * 8,
         "gate_f16_kernel": S * row + N * row + S * k * 8,
-        "gate_gemm_f32_kernel": S * row + N * row + S * N * 4,
+        "gate_f32_kernel": S * row + N * row + S * k * 8,
         "select_kernel": S * N * 4 + S * k * 8,
         "dispatch_copy_kernel": live_tokens * row + K * row + S * k * 8,
         "combine_kernel": K * row + S * row + S * k * 8,
@@ -492,7 +492,7 @@ def main():
                     "launches_timed": len(live),
                     "timed_in": "timed region" if dominant_live else "table pass"}
 
-    total_algo = algo_bytes["gate_gemm_f32_kernel" if wl.dtype == W.F32 else "gate_bf16_kernel"] \
+    total_algo = algo_bytes["gate_bf16_kernel"] \
         + algo_bytes["dispatch_copy_kernel"] + algo_bytes["combine_kernel"]
     result = {
         "metric": "routed tokens/sec (gate+aux_loss+dispatch+combine), 1 GPU",

@@ -2,9 +2,10 @@
 // (paper Section 3.1: gate network G with softmax, top-k experts per token, c_ie, m_i;
 // Section 4.1: per-destination-device volume).
 //
-// bf16 path (gate_bf16_kernel): the one dense contraction of the path, on the matrix cores.
-// v_mfma_f32_32x32x16_bf16 with A = a 32-expert block of W (from LDS) and B = 32 tokens of x
-// (straight from global memory, 64 contiguous bytes per lane and 64-element K chunk), so the
+// gate_bf16_kernel / gate_f16_kernel / gate_f32_kernel (one tile code, three element types): the one
+// dense contraction of the path, on the matrix cores.  v_mfma_f32_32x32x16_bf16 (or _f16, or four
+// v_mfma_f32_32x32x2_f32 for fp32 storage) with A = a 32-expert block of W and B = 32 tokens of x,
+// both from LDS tiles filled by coalesced loads of 128-byte K chunks, so the
 // accumulator tile is [expert][token]: lane l holds, for token (l & 31), the 16 experts
 //     e(v, l) = 8*(v>>2) + 4*(l>>5) + (v&3),   v = 0..15          (+32 per expert block)
 // and the lane pair (l, l^32) holds a token's whole score vector.  Softmax, top-k and the
@@ -12,7 +13,7 @@
 // only the per-expert probability sums need a reduction over the 32 token lanes.
 // The kernel is bound by the HBM read of x (intensity ~N flop/byte), not by the MFMA rate.
 //
-// fp32 path: plain fp32 FMA GEMM into a score buffer, then the same selection code.
+// tamoe_select runs the same selection code on a score matrix in memory (select_kernel).
 //
 // Determinism: probability sums are reduced in a fixed tree (lanes, wavefronts, workgroups);
 // counts are integers.  A second small kernel folds the per-workgroup partials.
@@ -272,8 +273,11 @@ __device__ __forceinline__ void store_block_partials(const float (*m_w)[NB * 32]
 }
 
 // KTAIL: d is not a multiple of the 64-element K chunk (the last chunk is partly out of range).
-// F16: the 2-byte elements are IEEE half precision instead of bfloat16; only the MFMA differs.
-template <int NB, int WAVES, bool KTAIL, bool F16>
+// ET: element type (TAMOE_BF16, TAMOE_F16, TAMOE_F32).  Rows are addressed in 2-byte units whatever the
+// type (d counts those units: twice the hidden size for fp32), a K chunk is 128 bytes of a row, and
+// tiles move as 16-byte pieces; only the MFMA differs.  For fp32 a piece holds four values and feeds
+// four v_mfma_f32_32x32x2_f32 (fp32 operands, fp32 accumulation) instead of one 32x32x16.
+template <int NB, int WAVES, bool KTAIL, int ET>
 __device__ __forceinline__ void gate_mfma_tile(
     const uint16_t* __restrict__ x, const uint16_t* __restrict__ w, int64_t S, int d, int N, int k,
     float* __restrict__ logits, int32_t* __restrict__ topk_idx, float* __restrict__ topk_w,
@@ -394,15 +398,28 @@ __device__ __forceinline__ void gate_mfma_tile(
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const vec16 b = *reinterpret_cast<const vec16*>(xl + i * 16);
+            if constexpr (ET == TAMOE_F32) {
+                vec16 a[NB];
 #pragma unroll
-            for (int nb = 0; nb < NB; ++nb) {
-                const vec16 a = *reinterpret_cast<const vec16*>(wl + nb * 32 * kLdsRow + i * 16);
-                if constexpr (F16)
-                    acc[nb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a),
-                                                                      __builtin_bit_cast(f16x8, b), acc[nb], 0, 0, 0);
-                else
-                    acc[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a),
-                                                                       __builtin_bit_cast(bf16x8, b), acc[nb], 0, 0, 0);
+                for (int nb = 0; nb < NB; ++nb) a[nb] = *reinterpret_cast<const vec16*>(wl + nb * 32 * kLdsRow + i * 16);
+                // consecutive MFMAs go to different accumulators
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+#pragma unroll
+                    for (int nb = 0; nb < NB; ++nb)
+                        acc[nb] = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a[nb][j]), __uint_as_float(b[j]),
+                                                                       acc[nb], 0, 0, 0);
+            } else {
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb) {
+                    const vec16 a = *reinterpret_cast<const vec16*>(wl + nb * 32 * kLdsRow + i * 16);
+                    if constexpr (ET == TAMOE_F16)
+                        acc[nb] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a),
+                                                                          __builtin_bit_cast(f16x8, b), acc[nb], 0, 0, 0);
+                    else
+                        acc[nb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a),
+                                                                           __builtin_bit_cast(bf16x8, b), acc[nb], 0, 0, 0);
+                }
             }
         }
     };
@@ -467,59 +484,22 @@ __device__ __forceinline__ void gate_mfma_tile(
 template <int NB, int WAVES, bool KTAIL>
 __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu((NB == 4 && WAVES < 4) ? 1 : 2)))
 void gate_bf16_kernel(TAMOE_GATE_ARGS) {
-    gate_mfma_tile<NB, WAVES, KTAIL, false>(x, w, S, d, N, k, logits, topk_idx, topk_w, m_part, c_part, n_blocks);
+    gate_mfma_tile<NB, WAVES, KTAIL, TAMOE_BF16>(x, w, S, d, N, k, logits, topk_idx, topk_w, m_part, c_part, n_blocks);
 }
 
 template <int NB, int WAVES, bool KTAIL>
 __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu((NB == 4 && WAVES < 4) ? 1 : 2)))
 void gate_f16_kernel(TAMOE_GATE_ARGS) {
-    gate_mfma_tile<NB, WAVES, KTAIL, true>(x, w, S, d, N, k, logits, topk_idx, topk_w, m_part, c_part, n_blocks);
+    gate_mfma_tile<NB, WAVES, KTAIL, TAMOE_F16>(x, w, S, d, N, k, logits, topk_idx, topk_w, m_part, c_part, n_blocks);
+}
+
+// fp32 storage: x and w point to floats, d counts 2-byte units (twice the hidden size)
+template <int NB, int WAVES, bool KTAIL>
+__global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu((NB == 4 && WAVES < 4) ? 1 : 2)))
+void gate_f32_kernel(TAMOE_GATE_ARGS) {
+    gate_mfma_tile<NB, WAVES, KTAIL, TAMOE_F32>(x, w, S, d, N, k, logits, topk_idx, topk_w, m_part, c_part, n_blocks);
 }
 #undef TAMOE_GATE_ARGS
-
-// fp32 scores: 64 tokens x N experts per workgroup, K in chunks of 32 through LDS, one fp32 FMA
-// per term in ascending K.
-template <int NB>
-__global__ __launch_bounds__(256) void gate_gemm_f32_kernel(const float* __restrict__ x, const float* __restrict__ w,
-                                                            int64_t S, int d, int N, float* __restrict__ logits) {
-    constexpr int ROWS = NB * 32;
-    constexpr int NE = ROWS / 4;
-    __shared__ float xs[64][33];
-    __shared__ float wsm[ROWS][33];
-    const int tid = threadIdx.x;
-    const int tx = tid & 63, ty = tid >> 6;
-    const int64_t t0 = (int64_t)blockIdx.x * 64;
-    float acc[NE];
-#pragma unroll
-    for (int i = 0; i < NE; ++i) acc[i] = 0.f;
-    for (int k0 = 0; k0 < d; k0 += 32) {
-        for (int q = tid; q < 64 * 32; q += 256) {
-            const int row = q >> 5, col = q & 31;
-            const int64_t t = t0 + row;
-            xs[row][col] = (t < S && k0 + col < d) ? x[(size_t)t * d + k0 + col] : 0.f;
-        }
-        for (int q = tid; q < ROWS * 32; q += 256) {
-            const int row = q >> 5, col = q & 31;
-            wsm[row][col] = (row < N && k0 + col < d) ? w[(size_t)row * d + k0 + col] : 0.f;
-        }
-        __syncthreads();
-#pragma unroll 4
-        for (int kk = 0; kk < 32; ++kk) {
-            const float xv = xs[tx][kk];
-#pragma unroll
-            for (int i = 0; i < NE; ++i) acc[i] = __builtin_fmaf(xv, wsm[ty + 4 * i][kk], acc[i]);
-        }
-        __syncthreads();
-    }
-    const int64_t t = t0 + tx;
-    if (t < S) {
-#pragma unroll
-        for (int i = 0; i < NE; ++i) {
-            const int e = ty + 4 * i;
-            if (e < N) logits[(size_t)t * N + e] = acc[i];
-        }
-    }
-}
 
 // Selection stage on a score matrix in memory: 4 wavefronts x 32 tokens per workgroup.
 template <int NB>
@@ -594,16 +574,23 @@ __global__ __launch_bounds__(256) void gate_finalize_kernel(const float* __restr
 
 // ---- host side ------------------------------------------------------------------------------
 
-template <int NB, bool F16>
+static const char* gate_kernel_name(int et) {
+    return et == TAMOE_F32 ? "gate_f32_kernel" : et == TAMOE_F16 ? "gate_f16_kernel" : "gate_bf16_kernel";
+}
+
+template <int NB, int ET>
 static void launch_gate_mfma(int waves, int64_t blocks, hipStream_t st, const uint16_t* x, const uint16_t* w,
                              int64_t S, int d, int N, int k, float* logits, int32_t* topk_idx, float* topk_w,
                              float* m_part, int32_t* c_part) {
     const dim3 grid((unsigned)blocks);
     const bool ktail = d % kKC != 0;
-    TraceScope tr(F16 ? "gate_f16_kernel" : "gate_bf16_kernel", st);
+    TraceScope tr(gate_kernel_name(ET), st);
 #define TAMOE_GATE_LAUNCH(WV, KT)                                                                                  \
     do {                                                                                                           \
-        if constexpr (F16)                                                                                         \
+        if constexpr (ET == TAMOE_F32)                                                                             \
+            gate_f32_kernel<NB, WV, KT><<<grid, dim3(WV * 64), 0, st>>>(x, w, S, d, N, k, logits, topk_idx, topk_w, \
+                                                                         m_part, c_part, (int)blocks);              \
+        else if constexpr (ET == TAMOE_F16)                                                                        \
             gate_f16_kernel<NB, WV, KT><<<grid, dim3(WV * 64), 0, st>>>(x, w, S, d, N, k, logits, topk_idx, topk_w, \
                                                                          m_part, c_part, (int)blocks);              \
         else                                                                                                       \
@@ -702,20 +689,26 @@ extern "C" int tamoe_gate(const void* x, const void* w, int dtype, int64_t S, in
     float* m_part = reinterpret_cast<float*>(static_cast<char*>(ws) + lay.m_part);
     int32_t* c_part = reinterpret_cast<int32_t*>(static_cast<char*>(ws) + lay.c_part);
     int64_t blocks = 0;
-    if (S > 0 && dtype != TAMOE_F32) {
+    if (S > 0) {
         const int waves = gate_waves(S, N);
         blocks = ceil_div(S, 32 * (int64_t)waves);
         if (blocks > 0x7fffffff) return fail(TAMOE_UNSUPPORTED, "%s: too many token tiles", fn);
+        // the tile code addresses rows in 2-byte units: an fp32 row of d values is a row of 2*d units
+        if (dtype == TAMOE_F32 && d > 0x3fffffff) return fail(TAMOE_UNSUPPORTED, "%s: d = %d is too large", fn, d);
+        const int d_units = dtype == TAMOE_F32 ? 2 * d : d;
         const uint16_t* xb = static_cast<const uint16_t*>(x);
         const uint16_t* wb = static_cast<const uint16_t*>(w);
 #define TAMOE_GATE_NB(NBV)                                                                                          \
     do {                                                                                                            \
-        if (dtype == TAMOE_F16)                                                                                     \
-            launch_gate_mfma<NBV, true>(waves, blocks, st, xb, wb, S, d, N, k, logits, topk_idx, topk_w, m_part,    \
-                                        c_part);                                                                    \
+        if (dtype == TAMOE_F32)                                                                                     \
+            launch_gate_mfma<NBV, TAMOE_F32>(waves, blocks, st, xb, wb, S, d_units, N, k, logits, topk_idx, topk_w, \
+                                             m_part, c_part);                                                       \
+        else if (dtype == TAMOE_F16)                                                                                \
+            launch_gate_mfma<NBV, TAMOE_F16>(waves, blocks, st, xb, wb, S, d_units, N, k, logits, topk_idx, topk_w, \
+                                             m_part, c_part);                                                       \
         else                                                                                                        \
-            launch_gate_mfma<NBV, false>(waves, blocks, st, xb, wb, S, d, N, k, logits, topk_idx, topk_w, m_part,   \
-                                         c_part);                                                                   \
+            launch_gate_mfma<NBV, TAMOE_BF16>(waves, blocks, st, xb, wb, S, d_units, N, k, logits, topk_idx,        \
+                                              topk_w, m_part, c_part);                                              \
     } while (0)
         if (N <= 32)
             TAMOE_GATE_NB(1);
@@ -724,25 +717,7 @@ extern "C" int tamoe_gate(const void* x, const void* w, int dtype, int64_t S, in
         else
             TAMOE_GATE_NB(4);
 #undef TAMOE_GATE_NB
-        if ((rc = check_launch(fn, dtype == TAMOE_F16 ? "gate_f16_kernel" : "gate_bf16_kernel")) != TAMOE_OK) return rc;
-    } else if (S > 0) {
-        float* lg = logits != nullptr ? logits : reinterpret_cast<float*>(static_cast<char*>(ws) + lay.logits);
-        const dim3 grid((unsigned)ceil_div(S, 64)), block(256);
-        const float* xf = static_cast<const float*>(x);
-        const float* wf = static_cast<const float*>(w);
-        {
-            TraceScope tr("gate_gemm_f32_kernel", st);
-            if (N <= 32)
-                gate_gemm_f32_kernel<1><<<grid, block, 0, st>>>(xf, wf, S, d, N, lg);
-            else if (N <= 64)
-                gate_gemm_f32_kernel<2><<<grid, block, 0, st>>>(xf, wf, S, d, N, lg);
-            else
-                gate_gemm_f32_kernel<4><<<grid, block, 0, st>>>(xf, wf, S, d, N, lg);
-        }
-        if ((rc = check_launch(fn, "gate_gemm_f32_kernel")) != TAMOE_OK) return rc;
-        blocks = ceil_div(S, 128);
-        launch_select(blocks, st, lg, S, N, k, topk_idx, topk_w, m_part, c_part);
-        if ((rc = check_launch(fn, "select_kernel")) != TAMOE_OK) return rc;
+        if ((rc = check_launch(fn, gate_kernel_name(dtype))) != TAMOE_OK) return rc;
     }
     {
         TraceScope tr("gate_finalize_kernel", st);

@@ -40,8 +40,6 @@ Workspace workspace_layout(int64_t S, int N, int k) {
     off = align_up(off + gb * N * sizeof(float), 256);
     w.c_part = off;
     off = align_up(off + gb * N * sizeof(int32_t), 256);
-    w.logits = off;
-    off = align_up(off + (size_t)S * N * sizeof(float), 256);
     w.tile_count = off;
     off = align_up(off + (size_t)k * count_tiles(S) * N * sizeof(int32_t), 256);
     w.total = off < 4096 ? 4096 : off;  // never less than the offset tables of tamoe_regroup

@@ -40,7 +40,6 @@ inline int64_t count_tiles(int64_t S) { return ceil_div(S, kCountTile); }
 struct Workspace {
     size_t m_part;      // float  [N][gate_blocks_max]   per-workgroup sums of gate probabilities
     size_t c_part;      // int32  [N][gate_blocks_max]   per-workgroup selection counts
-    size_t logits;      // float  [S][N]                 fp32-path scores when the caller wants none
     size_t tile_count;  // int32  [k][count_tiles][N]    pair counts, then their exclusive prefix
     size_t total;
 };
