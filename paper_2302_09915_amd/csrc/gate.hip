@@ -76,6 +76,123 @@ __device__ __forceinline__ bool ranks_before(float av, int ai, float bv, int bi)
     return av > bv || (av == bv && ai < bi);
 }
 
+// Writes the 32-token score tile of a wavefront to a row-major [S][N] matrix.  The accumulator
+// layout has one token per lane, so a direct store would write 16 bytes per lane, 512 bytes apart.
+// Each 32-expert block goes through a 32 x 32 tile of LDS owned by the wavefront (rows padded to 36
+// floats) and leaves as whole 128-byte row segments: eight lanes per row, eight rows per store
+// instruction.
+template <int NB>
+__device__ __forceinline__ void store_logits_tile(const float (&sc)[NB][16], int lane, int64_t token, int N,
+                                                  float* __restrict__ logits, float* tile, int64_t S) {
+    const int half = lane >> 5;
+    const int r = lane & 31;
+    const int64_t token0 = token - r;
+    const bool vec = (N & 3) == 0 && (reinterpret_cast<uintptr_t>(logits) & 15) == 0;
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            *reinterpret_cast<float4*>(&tile[r * kTileRow + 8 * q + 4 * half]) =
+                make_float4(sc[nb][4 * q], sc[nb][4 * q + 1], sc[nb][4 * q + 2], sc[nb][4 * q + 3]);
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int rr = i * 8 + (lane >> 3);
+            const int e = nb * 32 + (lane & 7) * 4;
+            const float4 v4 = *reinterpret_cast<const float4*>(&tile[rr * kTileRow + (lane & 7) * 4]);
+            const int64_t tg = token0 + rr;
+            if (tg < S && e < N) {
+                float* dst = logits + tg * N + e;
+                if (vec) {
+                    // streamed: 32 MiB of dirty lines left in L2 would be written back at the
+                    // end of the kernel, after the last wavefront, with nothing to overlap
+                    typedef float f32x4 __attribute__((ext_vector_type(4)));
+                    const f32x4 o = {v4.x, v4.y, v4.z, v4.w};
+                    __builtin_nontemporal_store(o, reinterpret_cast<f32x4*>(dst));
+                } else {
+                    dst[0] = v4.x;
+                    if (e + 1 < N) dst[1] = v4.y;
+                    if (e + 2 < N) dst[2] = v4.z;
+                    if (e + 3 < N) dst[3] = v4.w;
+                }
+            }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    }
+}
+
+// The reverse of store_logits_tile: reads the 32-token score tile of a wavefront from a row-major
+// [S][N] matrix (the sum of n_parts matrices part_stride floats apart, added in ascending order) as
+// whole 128-byte row segments and hands it over in the accumulator layout through the wavefront's
+// LDS tile.  Entries beyond S or N come back as -infinity.
+template <int NB>
+__device__ __forceinline__ void load_logits_tile(float (&sc)[NB][16], int lane, int64_t token, int N,
+                                                 const float* __restrict__ logits, int n_parts, size_t part_stride,
+                                                 float* tile, int64_t S) {
+    const int half = lane >> 5;
+    const int r = lane & 31;
+    const int64_t token0 = token - r;
+    const bool vec = (N & 3) == 0 && (part_stride & 3) == 0 && (reinterpret_cast<uintptr_t>(logits) & 15) == 0;
+    static_assert(kMaxKSplits <= 8, "the parts of a block are held in registers");
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+        // every load of the block is issued before the first sum: a loop that adds each part as it
+        // arrives pays one memory round trip per part
+        float4 part[4][kMaxKSplits];
+        bool inside[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int rr = i * 8 + (lane >> 3);
+            const int e = nb * 32 + (lane & 7) * 4;
+            const int64_t tg = token0 + rr;
+            inside[i] = tg < S && e < N;
+            const float* src = logits + (inside[i] ? tg * N + e : 0);
+#pragma unroll
+            for (int p = 0; p < kMaxKSplits; ++p) {
+                part[i][p] = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (inside[i] && p < n_parts) {
+                    if (vec) {
+                        part[i][p] = *reinterpret_cast<const float4*>(src + p * part_stride);
+                    } else {
+                        part[i][p].x = src[p * part_stride];
+                        if (e + 1 < N) part[i][p].y = src[p * part_stride + 1];
+                        if (e + 2 < N) part[i][p].z = src[p * part_stride + 2];
+                        if (e + 3 < N) part[i][p].w = src[p * part_stride + 3];
+                    }
+                }
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int rr = i * 8 + (lane >> 3);
+            const int e = nb * 32 + (lane & 7) * 4;
+            float4 v4 = part[i][0];
+#pragma unroll
+            for (int p = 1; p < kMaxKSplits; ++p) {  // ascending parts; absent parts are +0
+                v4.x += part[i][p].x;
+                v4.y += part[i][p].y;
+                v4.z += part[i][p].z;
+                v4.w += part[i][p].w;
+            }
+            if (!inside[i]) v4 = make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
+            if (inside[i] && e + 1 >= N) v4.y = -INFINITY;
+            if (inside[i] && e + 2 >= N) v4.z = -INFINITY;
+            if (inside[i] && e + 3 >= N) v4.w = -INFINITY;
+            *reinterpret_cast<float4*>(&tile[rr * kTileRow + (lane & 7) * 4]) = v4;
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const float4 v4 = *reinterpret_cast<const float4*>(&tile[r * kTileRow + 8 * q + 4 * half]);
+            sc[nb][4 * q] = v4.x;
+            sc[nb][4 * q + 1] = v4.y;
+            sc[nb][4 * q + 2] = v4.z;
+            sc[nb][4 * q + 3] = v4.w;
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    }
+}
+
 // Selection on a 32-token tile held in the accumulator layout described above.
 // sc[nb][v]: score of expert_of(nb, v, lane>>5) for token `token` (lane & 31 within the tile).
 // m_wave: LDS, [>= NB*32] floats owned by this wavefront; hist: LDS, [>= NB*32] ints of the block.
@@ -85,46 +202,7 @@ __device__ __forceinline__ void select_tile(float (&sc)[NB][16], int lane, int64
                                             float* __restrict__ topk_w, float* m_wave, int32_t* hist,
                                             float* tile, int64_t S) {
     const int half = lane >> 5;
-    if (logits != nullptr) {
-        // The accumulator layout has one token per lane, so a direct store would write 16 bytes
-        // per lane, 512 bytes apart.  Each 32-expert block goes through a 32 x 32 tile of LDS owned
-        // by the wavefront (rows padded to 36 floats) and leaves as whole 128-byte row segments:
-        // eight lanes per row, eight rows per store instruction.
-        const int r = lane & 31;
-        const int64_t token0 = token - r;
-        const bool vec = (N & 3) == 0 && (reinterpret_cast<uintptr_t>(logits) & 15) == 0;
-#pragma unroll
-        for (int nb = 0; nb < NB; ++nb) {
-#pragma unroll
-            for (int q = 0; q < 4; ++q)
-                *reinterpret_cast<float4*>(&tile[r * kTileRow + 8 * q + 4 * half]) =
-                    make_float4(sc[nb][4 * q], sc[nb][4 * q + 1], sc[nb][4 * q + 2], sc[nb][4 * q + 3]);
-            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int rr = i * 8 + (lane >> 3);
-                const int e = nb * 32 + (lane & 7) * 4;
-                const float4 v4 = *reinterpret_cast<const float4*>(&tile[rr * kTileRow + (lane & 7) * 4]);
-                const int64_t tg = token0 + rr;
-                if (tg < S && e < N) {
-                    float* dst = logits + tg * N + e;
-                    if (vec) {
-                        // streamed: 32 MiB of dirty lines left in L2 would be written back at the
-                        // end of the kernel, after the last wavefront, with nothing to overlap
-                        typedef float f32x4 __attribute__((ext_vector_type(4)));
-                        const f32x4 o = {v4.x, v4.y, v4.z, v4.w};
-                        __builtin_nontemporal_store(o, reinterpret_cast<f32x4*>(dst));
-                    } else {
-                        dst[0] = v4.x;
-                        if (e + 1 < N) dst[1] = v4.y;
-                        if (e + 2 < N) dst[2] = v4.z;
-                        if (e + 3 < N) dst[3] = v4.w;
-                    }
-                }
-            }
-            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-        }
-    }
+    if (logits != nullptr) store_logits_tile<NB>(sc, lane, token, N, logits, tile, S);
     if (N < NB * 32) {  // uniform
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb)
@@ -277,7 +355,10 @@ __device__ __forceinline__ void store_block_partials(const float (*m_w)[NB * 32]
 // type (d counts those units: twice the hidden size for fp32), a K chunk is 128 bytes of a row, and
 // tiles move as 16-byte pieces; only the MFMA differs.  For fp32 a piece holds four values and feeds
 // four v_mfma_f32_32x32x2_f32 (fp32 operands, fp32 accumulation) instead of one 32x32x16.
-template <int NB, int WAVES, bool KTAIL, int ET>
+// SPLIT: the workgroups of grid row blockIdx.y take the blockIdx.y-th share of the K chunks and write
+// their partial scores to logits + blockIdx.y * S * N instead of selecting; a select_kernel adds the
+// shares.  For batches so small that whole-K token tiles would leave most SIMDs idle.
+template <int NB, int WAVES, bool KTAIL, int ET, bool SPLIT = false>
 __device__ __forceinline__ void gate_mfma_tile(
     const uint16_t* __restrict__ x, const uint16_t* __restrict__ w, int64_t S, int d, int N, int k,
     float* __restrict__ logits, int32_t* __restrict__ topk_idx, float* __restrict__ topk_w,
@@ -305,13 +386,21 @@ __device__ __forceinline__ void gate_mfma_tile(
     for (int e = tid; e < ROWS; e += T) hist[e] = 0;
     for (int q = tid; q < WAVES * ROWS; q += T) (&m_w[0][0])[q] = 0.f;
 
-    const int n_chunks = (d + kKC - 1) / kKC;
+    const int all_chunks = (d + kKC - 1) / kKC;
+    int c_begin = 0, n_chunks = all_chunks;   // this workgroup's chunks: c_begin .. c_begin + n_chunks - 1
+    if constexpr (SPLIT) {
+        const int per = (all_chunks + (int)gridDim.y - 1) / (int)gridDim.y;
+        c_begin = (int)blockIdx.y * per;
+        n_chunks = all_chunks - c_begin < per ? all_chunks - c_begin : per;
+        if (n_chunks < 0) n_chunks = 0;       // a share past the end: its partial scores are zero
+    }
+    const int n_addr = n_chunks > 0 ? n_chunks : 1;  // for addresses only
     const vec16 zero = {0u, 0u, 0u, 0u};
     // Rows of x are a power-of-two pitch apart, so the same K chunk of every row falls into the
     // same few memory channels.  Workgroups would all walk K in step and queue on those channels;
     // instead workgroup b starts its walk at chunk (17 b) mod n_chunks and wraps around.  (A dot
     // product may be summed in any order; a token's scores depend on the order only in rounding.)
-    const int rot = (int)(((int64_t)blockIdx.x * 17) % n_chunks);
+    const int rot = (int)(((int64_t)blockIdx.x * 17) % n_addr);
 
     // Both tiles go global -> registers -> LDS -> MFMA operands.  Unit u of a thread is the
     // 16-byte piece (unit & 7) of tile row (unit >> 3), unit = tid + u * T: eight consecutive
@@ -346,8 +435,9 @@ __device__ __forceinline__ void gate_mfma_tile(
     const int piece = tid & 7;  // (unit & 7) is the same for every unit of a thread: T % 8 == 0
 
     auto chunk_at = [&](int step) {  // K chunk visited at pipeline step `step` (clamped past the end)
-        int c = (step < n_chunks ? step : n_chunks - 1) + rot;
-        return c >= n_chunks ? c - n_chunks : c;
+        int c = (step < n_addr ? step : n_addr - 1) + rot;
+        c = (c >= n_addr ? c - n_addr : c) + c_begin;
+        return c < all_chunks ? c : all_chunks - 1;
     };
     auto load_w = [&](int kc, vec16 (&dst)[WU]) {
         kc = chunk_at(kc);
@@ -472,8 +562,12 @@ __device__ __forceinline__ void gate_mfma_tile(
     // the K loop is over (its last stage ended with a barrier): x_lds is free, 9216 bytes per wavefront
     float* tile = reinterpret_cast<float*>(&x_lds[0][0]) + wave * (2 * 32 * kLdsRow / 4);
     static_assert(2 * 32 * kLdsRow >= 32 * kTileRow * 4, "logits tile must fit the wavefront's share of x_lds");
-    select_tile<NB>(sc, lane, token, token_ok, N, k, logits, topk_idx, topk_w, m_w[wave], hist, tile, S);
-    store_block_partials<NB, WAVES>(m_w, hist, N, n_blocks, m_part, c_part);
+    if constexpr (SPLIT) {
+        store_logits_tile<NB>(sc, lane, token, N, logits + (size_t)blockIdx.y * (size_t)S * N, tile, S);
+    } else {
+        select_tile<NB>(sc, lane, token, token_ok, N, k, logits, topk_idx, topk_w, m_w[wave], hist, tile, S);
+        store_block_partials<NB, WAVES>(m_w, hist, N, n_blocks, m_part, c_part);
+    }
 }
 
 #define TAMOE_GATE_ARGS                                                                                     \
@@ -499,34 +593,38 @@ __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu((NB 
 void gate_f32_kernel(TAMOE_GATE_ARGS) {
     gate_mfma_tile<NB, WAVES, KTAIL, TAMOE_F32>(x, w, S, d, N, k, logits, topk_idx, topk_w, m_part, c_part, n_blocks);
 }
+
+// fp32 storage, small batches: one wavefront per workgroup, K split over grid rows (see SPLIT above)
+template <int NB, bool KTAIL>
+__global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(1)))
+void gate_f32_split_kernel(TAMOE_GATE_ARGS) {
+    gate_mfma_tile<NB, 1, KTAIL, TAMOE_F32, true>(x, w, S, d, N, k, logits, topk_idx, topk_w, m_part, c_part, n_blocks);
+}
 #undef TAMOE_GATE_ARGS
 
-// Selection stage on a score matrix in memory: 4 wavefronts x 32 tokens per workgroup.
+// Selection stage on a score matrix in memory: 4 wavefronts x 32 tokens per workgroup.  The scores
+// may arrive as n_parts partial matrices (the K shares of a split gate, part_stride floats apart),
+// which are added in ascending order; logits_out (may be NULL) then receives the sums.
 template <int NB>
-__global__ __launch_bounds__(256) void select_kernel(const float* __restrict__ logits, int64_t S, int N, int k,
+__global__ __launch_bounds__(256) void select_kernel(const float* __restrict__ logits, int n_parts, size_t part_stride,
+                                                     float* __restrict__ logits_out, int64_t S, int N, int k,
                                                      int32_t* __restrict__ topk_idx, float* __restrict__ topk_w,
                                                      float* __restrict__ m_part, int32_t* __restrict__ c_part,
                                                      int n_blocks) {
     constexpr int ROWS = NB * 32;
     __shared__ float m_w[4][ROWS];
     __shared__ int32_t hist[ROWS];
+    __shared__ __attribute__((aligned(16))) float out_tile[4][32 * kTileRow];
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
-    const int half = lane >> 5;
     const int64_t token = ((int64_t)blockIdx.x * 4 + wave) * 32 + (lane & 31);
     const bool token_ok = token < S;
     for (int e = tid; e < ROWS; e += 256) hist[e] = 0;
     for (int q = tid; q < 4 * ROWS; q += 256) (&m_w[0][0])[q] = 0.f;
     __syncthreads();
     float sc[NB][16];
-#pragma unroll
-    for (int nb = 0; nb < NB; ++nb)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int e = expert_of(nb, v, half);
-            sc[nb][v] = (token_ok && e < N) ? logits[(size_t)token * N + e] : -INFINITY;
-        }
-    select_tile<NB>(sc, lane, token, token_ok, N, k, nullptr, topk_idx, topk_w, m_w[wave], hist, nullptr, S);
+    load_logits_tile<NB>(sc, lane, token, N, logits, n_parts, part_stride, out_tile[wave], S);
+    select_tile<NB>(sc, lane, token, token_ok, N, k, logits_out, topk_idx, topk_w, m_w[wave], hist, out_tile[wave], S);
     store_block_partials<NB, 4>(m_w, hist, N, n_blocks, m_part, c_part);
 }
 
@@ -611,16 +709,20 @@ static void launch_gate_mfma(int waves, int64_t blocks, hipStream_t st, const ui
 #undef TAMOE_GATE_LAUNCH
 }
 
-static void launch_select(int64_t blocks, hipStream_t st, const float* logits, int64_t S, int N, int k,
-                          int32_t* topk_idx, float* topk_w, float* m_part, int32_t* c_part) {
+static void launch_select(int64_t blocks, hipStream_t st, const float* logits, int n_parts, size_t part_stride,
+                          float* logits_out, int64_t S, int N, int k, int32_t* topk_idx, float* topk_w, float* m_part,
+                          int32_t* c_part) {
     const dim3 grid((unsigned)blocks), block(256);
     TraceScope tr("select_kernel", st);
     if (N <= 32)
-        select_kernel<1><<<grid, block, 0, st>>>(logits, S, N, k, topk_idx, topk_w, m_part, c_part, (int)blocks);
+        select_kernel<1><<<grid, block, 0, st>>>(logits, n_parts, part_stride, logits_out, S, N, k, topk_idx, topk_w,
+                                                 m_part, c_part, (int)blocks);
     else if (N <= 64)
-        select_kernel<2><<<grid, block, 0, st>>>(logits, S, N, k, topk_idx, topk_w, m_part, c_part, (int)blocks);
+        select_kernel<2><<<grid, block, 0, st>>>(logits, n_parts, part_stride, logits_out, S, N, k, topk_idx, topk_w,
+                                                 m_part, c_part, (int)blocks);
     else
-        select_kernel<4><<<grid, block, 0, st>>>(logits, S, N, k, topk_idx, topk_w, m_part, c_part, (int)blocks);
+        select_kernel<4><<<grid, block, 0, st>>>(logits, n_parts, part_stride, logits_out, S, N, k, topk_idx, topk_w,
+                                                 m_part, c_part, (int)blocks);
 }
 
 static int check_select_outputs(const char* fn, int64_t S, int32_t* topk_idx, float* topk_w, float* m,
@@ -659,7 +761,7 @@ extern "C" int tamoe_select(const float* logits, int64_t S, int N, int P, int k,
     int32_t* c_part = reinterpret_cast<int32_t*>(static_cast<char*>(ws) + lay.c_part);
     const int64_t blocks = ceil_div(S, 128);
     if (blocks > 0) {
-        launch_select(blocks, st, logits, S, N, k, topk_idx, topk_w, m_part, c_part);
+        launch_select(blocks, st, logits, 1, 0, nullptr, S, N, k, topk_idx, topk_w, m_part, c_part);
         if ((rc = check_launch(fn, "select_kernel")) != TAMOE_OK) return rc;
     }
     {
@@ -682,7 +784,7 @@ extern "C" int tamoe_gate(const void* x, const void* w, int dtype, int64_t S, in
         if ((rc = check_ptr(fn, "x", x, 16)) != TAMOE_OK) return rc;
         if ((rc = check_ptr(fn, "w", w, 16)) != TAMOE_OK) return rc;
     }
-    const Workspace lay = workspace_layout(S, N, k);
+    const Workspace lay = workspace_layout(S, N, k, dtype);
     if ((rc = check_select_outputs(fn, S, topk_idx, topk_w, m, c_expert, c_device, ws, ws_bytes, lay)) != TAMOE_OK)
         return rc;
     hipStream_t st = static_cast<hipStream_t>(stream);
@@ -698,6 +800,37 @@ extern "C" int tamoe_gate(const void* x, const void* w, int dtype, int64_t S, in
         const int d_units = dtype == TAMOE_F32 ? 2 * d : d;
         const uint16_t* xb = static_cast<const uint16_t*>(x);
         const uint16_t* wb = static_cast<const uint16_t*>(w);
+        const int splits = gate_k_splits(dtype, S, d_units, waves);
+        if (splits > 1) {
+            // fp32, few token tiles: K shares on grid rows, partial scores in the workspace, then the
+            // selection kernel adds them
+            float* part = reinterpret_cast<float*>(static_cast<char*>(ws) + lay.part_logits);
+            const dim3 grid((unsigned)blocks, (unsigned)splits);
+            const bool ktail = d_units % kKC != 0;
+            {
+                TraceScope tr("gate_f32_split_kernel", st);
+#define TAMOE_SPLIT(NBV)                                                                                            \
+    do {                                                                                                            \
+        if (ktail)                                                                                                  \
+            gate_f32_split_kernel<NBV, true><<<grid, dim3(64), 0, st>>>(xb, wb, S, d_units, N, k, part, topk_idx,   \
+                                                                         topk_w, m_part, c_part, (int)blocks);       \
+        else                                                                                                        \
+            gate_f32_split_kernel<NBV, false><<<grid, dim3(64), 0, st>>>(xb, wb, S, d_units, N, k, part, topk_idx,  \
+                                                                          topk_w, m_part, c_part, (int)blocks);      \
+    } while (0)
+                if (N <= 32)
+                    TAMOE_SPLIT(1);
+                else if (N <= 64)
+                    TAMOE_SPLIT(2);
+                else
+                    TAMOE_SPLIT(4);
+#undef TAMOE_SPLIT
+            }
+            if ((rc = check_launch(fn, "gate_f32_split_kernel")) != TAMOE_OK) return rc;
+            blocks = ceil_div(S, 128);
+            launch_select(blocks, st, part, splits, (size_t)S * N, logits, S, N, k, topk_idx, topk_w, m_part, c_part);
+            if ((rc = check_launch(fn, "select_kernel")) != TAMOE_OK) return rc;
+        } else {
 #define TAMOE_GATE_NB(NBV)                                                                                          \
     do {                                                                                                            \
         if (dtype == TAMOE_F32)                                                                                     \
@@ -717,7 +850,8 @@ extern "C" int tamoe_gate(const void* x, const void* w, int dtype, int64_t S, in
         else
             TAMOE_GATE_NB(4);
 #undef TAMOE_GATE_NB
-        if ((rc = check_launch(fn, gate_kernel_name(dtype))) != TAMOE_OK) return rc;
+            if ((rc = check_launch(fn, gate_kernel_name(dtype))) != TAMOE_OK) return rc;
+        }
     }
     {
         TraceScope tr("gate_finalize_kernel", st);

@@ -32,7 +32,16 @@ int gate_waves(int64_t S, int N) {
     return 1;
 }
 
-Workspace workspace_layout(int64_t S, int N, int k) {
+int gate_k_splits(int dtype, int64_t S, int d_units, int waves) {
+    if (dtype != TAMOE_F32 || waves != 1 || S <= 0 || S >= kSplitMaxTokens) return 1;
+    const int64_t tiles = ceil_div(S, 32);
+    const int64_t room = 1024 / tiles;                    // wavefronts the device still has room for, per tile
+    const int64_t by_chunks = ceil_div(d_units, 64) / 8;  // at least eight 128-byte chunks per share
+    const int64_t s = room < by_chunks ? room : by_chunks;
+    return (int)(s < 1 ? 1 : (s > kMaxKSplits ? kMaxKSplits : s));
+}
+
+Workspace workspace_layout(int64_t S, int N, int k, int dtype) {
     Workspace w{};
     size_t off = 0;
     const size_t gb = (size_t)gate_blocks_max(S);
@@ -42,6 +51,13 @@ Workspace workspace_layout(int64_t S, int N, int k) {
     off = align_up(off + gb * N * sizeof(int32_t), 256);
     w.tile_count = off;
     off = align_up(off + (size_t)k * count_tiles(S) * N * sizeof(int32_t), 256);
+    // last, so that the other offsets do not depend on the storage type; sized for the largest batch
+    // that can be split, so that the total grows with S
+    w.part_logits = off;
+    if (dtype == TAMOE_F32) {
+        const int64_t rows = S < kSplitMaxTokens ? S : kSplitMaxTokens;
+        off = align_up(off + (size_t)kMaxKSplits * rows * N * sizeof(float), 256);
+    }
     w.total = off < 4096 ? 4096 : off;  // never less than the offset tables of tamoe_regroup
     return w;
 }
@@ -183,9 +199,9 @@ extern "C" int tamoe_version(void) { return TAMOE_VERSION; }
 extern "C" const char* tamoe_last_error(void) { return g_err; }
 
 extern "C" size_t tamoe_workspace_bytes(int64_t S, int d, int N, int P, int k, int dtype) {
-    (void)d; (void)P; (void)dtype;
+    (void)d; (void)P;
     if (S < 0 || N <= 0 || k <= 0) return 0;
-    return workspace_layout(S, N, k).total;
+    return workspace_layout(S, N, k, dtype).total;
 }
 
 // Setup stage.  Per-level means of the profiled inverse bandwidths, then the closed-form target

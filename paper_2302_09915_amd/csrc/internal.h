@@ -29,6 +29,11 @@ inline int elem_bytes(int dtype) { return dtype == TAMOE_F32 ? 4 : 2; }
 // per wavefront).  More wavefronts per workgroup share one LDS copy of the W tile; fewer give
 // more workgroups when S is small.
 int gate_waves(int64_t S, int N);
+// K-split gate (fp32 storage, one-wavefront workgroups, fewer token tiles than half the SIMDs): the
+// number of K shares, 1 = no split.  d_units: row length in 2-byte units.
+constexpr int kMaxKSplits = 8;
+constexpr int64_t kSplitMaxTokens = 16384;  // above this the token tiles alone fill the device
+int gate_k_splits(int dtype, int64_t S, int d_units, int waves);
 // Upper bound of the number of gate workgroups over every choice of waves.
 inline int64_t gate_blocks_max(int64_t S) { return ceil_div(S, 32); }
 
@@ -41,9 +46,12 @@ struct Workspace {
     size_t m_part;      // float  [N][gate_blocks_max]   per-workgroup sums of gate probabilities
     size_t c_part;      // int32  [N][gate_blocks_max]   per-workgroup selection counts
     size_t tile_count;  // int32  [k][count_tiles][N]    pair counts, then their exclusive prefix
+    size_t part_logits; // float  [kMaxKSplits][S][N]    partial scores of a K-split gate (small S only)
     size_t total;
 };
-Workspace workspace_layout(int64_t S, int N, int k);
+// dtype: only fp32 storage adds the partial-score region (the gate's K split); every other region sits
+// at the same offset for every storage type.
+Workspace workspace_layout(int64_t S, int N, int k, int dtype = TAMOE_BF16);
 
 // log2(v) if v is a power of two, else -1.
 inline int pow2_shift(int v) {
