@@ -152,7 +152,8 @@ int tamoe_ring_table(const double* beta_link, const double* alpha_link, int P, d
 int tamoe_minmax_pattern(const double* alpha_row, const double* beta_row, int P, int N, int k, int64_t S,
                          double bytes_per_row, double* c_hat, double* t_comm);
 
-/* Bytes of device workspace that any of the device functions below needs for this shape. */
+/* Bytes of device workspace that any of the device functions below needs for this shape and storage
+ * type (fp32 storage adds room for the partial scores of the gate's K split).  Grows with S. */
 size_t tamoe_workspace_bytes(int64_t S, int d, int N, int P, int k, int dtype);
 
 /*
