@@ -13,32 +13,54 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libtamoe.so")
 
 HIPCC_FLAGS = [
-    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
     # the compiler must not form packed fp32 instructions from ordinary float code
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wall", "-Wextra", "-Wno-unused-parameter",
 ]
+OBJ_DIR = os.path.join(HERE, "_build")
 
 
 def sources():
     return sorted(glob.glob(os.path.join(CSRC, "*.hip")) + glob.glob(os.path.join(CSRC, "*.cpp")))
 
 
-def build(verbose: bool = False) -> str:
-    hipcc = shutil.which("hipcc") or "/opt/rocm/bin/hipcc"
-    cmd = [hipcc, *HIPCC_FLAGS, "-I", os.path.join(ROOT, "include"), "-I", CSRC]
-    for s in sources():
-        # .cpp files hold host code only but share the HIP headers
-        cmd += (["-x", "hip", s])
-    cmd += ["-o", LIB]
+def _compile(hipcc: str, src: str, verbose: bool):
+    obj = os.path.join(OBJ_DIR, os.path.basename(src) + ".o")
+    # .cpp files hold host code only but share the HIP headers
+    cmd = [hipcc, *HIPCC_FLAGS, "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-x", "hip", "-c", src, "-o", obj]
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, capture_output=True, text=True)
+    return obj, res
+
+
+def build(verbose: bool = False, jobs: int = 0) -> str:
+    """Compiles every source of csrc/ to an object (in parallel: the gate's tile code is instantiated
+    in one translation unit per element type) and links libtamoe.so."""
+    from concurrent.futures import ThreadPoolExecutor
+
+    hipcc = shutil.which("hipcc") or "/opt/rocm/bin/hipcc"
+    os.makedirs(OBJ_DIR, exist_ok=True)
+    srcs = sources()
+    jobs = jobs or max(1, min(len(srcs), os.cpu_count() or 1, 8))
+    with ThreadPoolExecutor(max_workers=jobs) as pool:
+        done = list(pool.map(lambda src: _compile(hipcc, src, verbose), srcs))
+    objs = []
+    for obj, res in done:
+        if res.returncode != 0:
+            sys.stderr.write(res.stdout + res.stderr)
+            raise RuntimeError("hipcc failed building libtamoe.so")
+        if verbose and res.stderr.strip():
+            sys.stderr.write(res.stderr)
+        objs.append(obj)
+    link = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", LIB]
+    if verbose:
+        print(" ".join(link), flush=True)
+    res = subprocess.run(link, capture_output=True, text=True)
     if res.returncode != 0:
         sys.stderr.write(res.stdout + res.stderr)
-        raise RuntimeError("hipcc failed building libtamoe.so")
-    if verbose and res.stderr.strip():
-        sys.stderr.write(res.stderr)
+        raise RuntimeError("hipcc failed linking libtamoe.so")
     return LIB
 
 
