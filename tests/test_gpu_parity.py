@@ -1,8 +1,8 @@
 """Parity of the HIP path (through the C ABI) against the CPU oracle on a real MI355X.
 
 Staging (same seeded inputs on both sides):
-  A  scores: GPU fp32 logits vs oracle fp64 logits, normwise and elementwise, tol 1e-3 (bf16
-     inputs) / 1e-5 (fp32 inputs);
+  A  scores: GPU fp32 logits vs oracle fp64 logits, normwise and elementwise, tol 1e-3 (bf16 and
+     half-precision inputs) / 1e-5 (fp32 inputs);
   B  everything decided from the scores is compared with the oracle re-run on the GPU's own fp32
      scores: indices, counts, slots, kept, offsets, per-device rows bit-exact; weights, mean
      probabilities and the losses within 1e-5 relative;
@@ -10,7 +10,7 @@ Staging (same seeded inputs on both sides):
   D  combine: against the oracle's fp64 sum of the same rows with the GPU's fp32 weights: within
      half an ulp of the storage type plus the fp32 accumulation error, and equal to the oracle's
      once-rounded output in all but a tiny fraction of elements (1-ulp flips at rounding ties);
-  E  end to end: the loss from the oracle's own scores vs the GPU's, 1e-3 (bf16) / 1e-5 (fp32).
+  E  end to end: the loss from the oracle's own scores vs the GPU's, 1e-3 (2-byte storage) / 1e-5 (fp32).
 """
 import math
 
