@@ -298,7 +298,7 @@ def _random_shape(i):
     return dtype, S, d, N, P, k, cf
 
 
-@pytest.mark.parametrize("i", range(24))
+@pytest.mark.parametrize("i", range(40))
 def test_random_shapes(T, oracle, i):
     dtype, S, d, N, P, k, cf = _random_shape(i)
     print(f"shape {i}: dtype={dtype} S={S} d={d} N={N} P={P} k={k} cf={cf}", flush=True)
