@@ -25,8 +25,22 @@ def sources():
     return sorted(glob.glob(os.path.join(CSRC, "*.hip")) + glob.glob(os.path.join(CSRC, "*.cpp")))
 
 
-def _compile(hipcc: str, src: str, verbose: bool):
+def _headers():
+    return glob.glob(os.path.join(CSRC, "*.h")) + glob.glob(os.path.join(ROOT, "include", "*.h"))
+
+
+def _fresh(obj: str, src: str) -> bool:
+    """True if obj is newer than its source and every header."""
+    if not os.path.exists(obj):
+        return False
+    t = os.path.getmtime(obj)
+    return all(os.path.getmtime(f) < t for f in [src, *_headers()])
+
+
+def _compile(hipcc: str, src: str, verbose: bool, incremental: bool = False):
     obj = os.path.join(OBJ_DIR, os.path.basename(src) + ".o")
+    if incremental and _fresh(obj, src):
+        return obj, subprocess.CompletedProcess([], 0, "", "")
     # .cpp files hold host code only but share the HIP headers
     cmd = [hipcc, *HIPCC_FLAGS, "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-x", "hip", "-c", src, "-o", obj]
     if verbose:
@@ -35,9 +49,10 @@ def _compile(hipcc: str, src: str, verbose: bool):
     return obj, res
 
 
-def build(verbose: bool = False, jobs: int = 0) -> str:
+def build(verbose: bool = False, jobs: int = 0, incremental: bool = False) -> str:
     """Compiles every source of csrc/ to an object (in parallel: the gate's tile code is instantiated
-    in one translation unit per element type) and links libtamoe.so."""
+    in one translation unit per element type) and links libtamoe.so.  incremental: keep the objects
+    that are newer than their source and every header (for development; the default rebuilds all)."""
     from concurrent.futures import ThreadPoolExecutor
 
     hipcc = shutil.which("hipcc") or "/opt/rocm/bin/hipcc"
@@ -45,7 +60,7 @@ def build(verbose: bool = False, jobs: int = 0) -> str:
     srcs = sources()
     jobs = jobs or max(1, min(len(srcs), os.cpu_count() or 1, 8))
     with ThreadPoolExecutor(max_workers=jobs) as pool:
-        done = list(pool.map(lambda src: _compile(hipcc, src, verbose), srcs))
+        done = list(pool.map(lambda src: _compile(hipcc, src, verbose, incremental), srcs))
     objs = []
     for obj, res in done:
         if res.returncode != 0:
@@ -65,4 +80,4 @@ def build(verbose: bool = False, jobs: int = 0) -> str:
 
 
 if __name__ == "__main__":
-    print(build(verbose=True))
+    print(build(verbose=True, incremental="--incremental" in sys.argv[1:]))

@@ -165,19 +165,22 @@ def full_parity(T, oracle, spec, x_np, w_np, penalty, cap, sample=None):
     ref_send = oracle.scatter(x_np, dt, ref["slot"], ref["K"])
     np.testing.assert_array_equal(send, ref_send)
 
-    # D: combine on the sampled tokens, identity expert, GPU weights
-    slot_s = ref["slot"][rows]
-    used = np.unique(slot_s[slot_s >= 0])
-    remap = -np.ones(max(ref["K"], 1), dtype=np.int32)
-    remap[used] = np.arange(len(used), dtype=np.int32)
-    slot_sub = np.where(slot_s >= 0, remap[np.maximum(slot_s, 0)], -1).astype(np.int32)
-    recv_sub = np.ascontiguousarray(ref_send[used]) if len(used) else np.zeros((0, d), dtype=ref_send.dtype)
-    wg = g["topk_w"][rows].astype(np.float64)
-    y_exact, y_ref = oracle.combine(recv_sub if len(used) else np.zeros((1, d), dtype=ref_send.dtype),
-                                    dt, slot_sub, wg)
-    xv = np.abs(W.storage_to_f64(np.ascontiguousarray(x_np[rows]), dt))
-    mag = (np.where(slot_s >= 0, np.abs(wg), 0.0).sum(axis=1))[:, None] * xv
-    check_combine(g["y"][rows], y_exact, y_ref, mag, dt, k)
+    # D: combine on the sampled tokens, identity expert, GPU weights; in blocks of tokens so that the
+    # fp64 copies of a full-size batch stay small
+    block = max(1, (1 << 25) // max(d, 1))
+    for r0 in range(0, len(rows), block):
+        rb = rows[r0:r0 + block]
+        slot_s = ref["slot"][rb]
+        used = np.unique(slot_s[slot_s >= 0])
+        remap = -np.ones(max(ref["K"], 1), dtype=np.int32)
+        remap[used] = np.arange(len(used), dtype=np.int32)
+        slot_sub = np.where(slot_s >= 0, remap[np.maximum(slot_s, 0)], -1).astype(np.int32)
+        recv_sub = np.ascontiguousarray(ref_send[used]) if len(used) else np.zeros((1, d), dtype=ref_send.dtype)
+        wg = g["topk_w"][rb].astype(np.float64)
+        y_exact, y_ref = oracle.combine(recv_sub, dt, slot_sub, wg)
+        xv = np.abs(W.storage_to_f64(np.ascontiguousarray(x_np[rb]), dt))
+        mag = (np.where(slot_s >= 0, np.abs(wg), 0.0).sum(axis=1))[:, None] * xv
+        check_combine(g["y"][rb], y_exact, y_ref, mag, dt, k)
 
     # E: end to end, oracle on its own scores (needs all tokens' scores: only when not sampled)
     if sample is None and S > 0:
@@ -237,18 +240,51 @@ def test_paper_shapes_parity(T, oracle, name):
     full_parity(T, oracle, spec_of(wl), inp["x"], inp["w"], pen.astype(np.float64), cap)
 
 
-def test_large_config_parity_sampled(T, oracle):
-    """Full size, the launch configuration the benchmark times.  Scores and combine are checked
-    on a sample of tokens; selection, slots and the send buffer on every token."""
+ROUTED_KEYS = ("topk_idx", "topk_w", "m", "c_expert", "c_device", "slot", "kept_expert", "expert_offset",
+               "send_count_dev", "y")
+
+
+@pytest.mark.parametrize("cap_mode", [0, 1])
+def test_large_config_parity(T, oracle, cap_mode):
+    """Full size, the launch configuration the benchmark times: every stage on every token, under the
+    uniform capacity (rank 0) and under the capacity proportional to the target pattern (an interior
+    rank; a random gate then loses a large share of its pairs).  The benchmark calls the gate without
+    the optional scores output: that call must give the same bits as the one checked here."""
     wl = W.WORKLOADS["large"]
     oracle.set_threads(oracle.max_threads())
     inp = W.make_inputs(wl)
     beta, level = W.topology(wl)
-    c_hat, pen, cap = T.tamoe_topo_pattern(beta, level, wl.P, wl.N, 0, wl.k, wl.S, wl.capacity_factor, 0)
-    rng = np.random.default_rng(99)
-    sample = np.sort(np.concatenate([rng.choice(wl.S, 1500, replace=False), [0, 31, 32, 127, 128, wl.S - 1]]))
-    sample = np.unique(sample)
-    full_parity(T, oracle, spec_of(wl), inp["x"], inp["w"], pen.astype(np.float64), cap, sample=sample)
+    rank = 0 if cap_mode == 0 else wl.P // 2 + 1
+    c_hat, pen, cap = T.tamoe_topo_pattern(beta, level, wl.P, wl.N, rank, wl.k, wl.S, wl.capacity_factor, cap_mode)
+    g, ref = full_parity(T, oracle, spec_of(wl), inp["x"], inp["w"], pen.astype(np.float64), cap)
+    if cap_mode == 1:
+        assert ref["K"] < 0.75 * wl.k * wl.S, "the proportional capacity must drop pairs of a random gate"
+        assert (ref["slot"] < 0).all(axis=1).any(), "some token must lose every choice"
+    send_a = g.pop("send_t")[: g["K"]].view(torch.int16).cpu()
+    b = gpu_path(T, spec_of(wl), inp["x"], inp["w"], pen, cap, want_logits=False)
+    for key in ROUTED_KEYS:
+        np.testing.assert_array_equal(g[key], b[key], err_msg=key)
+    assert g["l_topo"] == b["l_topo"] and g["l_aux"] == b["l_aux"] and g["K"] == b["K"]
+    assert torch.equal(send_a, b["send_t"][: b["K"]].view(torch.int16).cpu())
+
+
+# Shapes that reach the gate's eight-wavefront workgroups (more than 32 experts and at least 65 281
+# tokens) in every instantiation: three storage types x (up to 64 | up to 128 experts) x (hidden size
+# a multiple of the 128-byte K chunk | with a K tail).  Small hidden sizes keep the oracle cheap.
+@pytest.mark.parametrize("dtype,d,N,P,k", [
+    (W.BF16, 128, 64, 64, 1), (W.BF16, 200, 48, 16, 2), (W.BF16, 192, 128, 64, 2), (W.BF16, 72, 96, 8, 3),
+    (W.F16, 64, 64, 8, 2), (W.F16, 88, 40, 10, 1), (W.F16, 128, 128, 64, 2), (W.F16, 264, 96, 32, 2),
+    (W.F32, 96, 64, 64, 2), (W.F32, 100, 33, 11, 1), (W.F32, 64, 128, 64, 2), (W.F32, 36, 96, 96, 4),
+])
+def test_eight_wavefront_gate_shapes(T, oracle, dtype, d, N, P, k):
+    S = 66000                                   # 258 workgroups of 256 tokens, the last one ragged
+    oracle.set_threads(oracle.max_threads())
+    rng = np.random.default_rng(7 * d + N)
+    x = W.to_storage(rng.standard_normal((S, d)).astype(np.float32), dtype)
+    w = W.to_storage((rng.standard_normal((N, d)) / math.sqrt(d)).astype(np.float32), dtype)
+    beta = rng.uniform(1.0, 9.0, size=(P, P))
+    c_hat, pen, cap = T.tamoe_topo_pattern(beta, None, P, N, P // 3, k, S, 1.1, (d // 8) % 2)
+    full_parity(T, oracle, {"dtype": dtype, "N": N, "P": P, "k": k}, x, w, pen.astype(np.float64), cap)
 
 
 # ---------------------------------------------------------------------------
@@ -433,8 +469,7 @@ def test_runs_are_bitwise_repeatable_and_logits_are_optional(T):
     _, pen, cap = T.tamoe_topo_pattern(beta, level, wl.P, wl.N, 0, wl.k, wl.S, wl.capacity_factor, 0)
     a = gpu_path(T, spec_of(wl), inp["x"], inp["w"], pen, cap, want_logits=True)
     b = gpu_path(T, spec_of(wl), inp["x"], inp["w"], pen, cap, want_logits=False)
-    for key in ("topk_idx", "topk_w", "m", "c_expert", "c_device", "slot", "kept_expert", "expert_offset",
-                "send_count_dev", "y"):
+    for key in ROUTED_KEYS:
         np.testing.assert_array_equal(a[key], b[key], err_msg=key)
     assert a["l_topo"] == b["l_topo"] and a["K"] == b["K"]
     assert torch.equal(a["send_t"][: a["K"]].view(torch.int16), b["send_t"][: b["K"]].view(torch.int16))
