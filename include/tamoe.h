@@ -219,6 +219,23 @@ int tamoe_dispatch(const void* x, const int32_t* topk_idx, const int32_t* cap, i
                    void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * tamoe_dispatch for callers that cannot allocate device memory or carry a workspace (code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc): same arguments, outputs and
+ * kernels as tamoe_dispatch without `ws`.  The pair counters live in an array inside the library's
+ * own device image, TAMOE_STATIC_SCRATCH_BYTES per device, held until the process ends; the call
+ * allocates and frees nothing.  Limit: k * ceil(S/1024) * N * 4 <= TAMOE_STATIC_SCRATCH_BYTES
+ * (k = 2, N = 128: S <= 1 048 576), else TAMOE_UNSUPPORTED.  Every call on a device uses that
+ * device's one array: calls that overlap on one device (two streams, two threads) race; order them.
+ * The array's content between calls is garbage (every counter is written before it is read).
+ * The first call on a device looks up the array's address, so make that call outside a capture.
+ */
+#define TAMOE_STATIC_SCRATCH_BYTES (1 << 20)
+int tamoe_dispatch_static(const void* x, const int32_t* topk_idx, const int32_t* cap, int dtype,
+                          int64_t S, int d, int N, int P, int k,
+                          void* send, int32_t* slot, int32_t* kept_expert, int32_t* expert_offset,
+                          int32_t* send_count_dev, void* stream);
+
+/*
  * Weighted combine (Section 3.1: the output y of the layer aggregates the computed results).
  * recv holds the expert outputs in the row order of the send buffer.
  *   y[t][:] = sum over j = 0..k-1 with slot[t][j] >= 0 of topk_w[t][j] * recv[slot[t][j]][:]

@@ -38,6 +38,7 @@ EXPORTS = (
     "tamoe_gate_bwd", "tamoe_combine_bwd", "tamoe_dispatch_bwd", "tamoe_regroup",
     "tamoe_tree_levels", "tamoe_ring_table", "tamoe_minmax_pattern",
     "tamoe_penalty", "tamoe_renorm_topk", "tamoe_renorm_topk_bwd", "tamoe_dispatch_padded",
+    "tamoe_dispatch_static",
     "tamoe_trace_start", "tamoe_trace_filter", "tamoe_trace_stop", "tamoe_trace_get", "tamoe_trace_clear", "tamoe_copy_probe", "tamoe_mix_probe",
 )
 
@@ -78,6 +79,8 @@ def lib() -> ctypes.CDLL:
     L.tamoe_aux_loss.argtypes = [vp, vp, vp, i32, i32, i64, vp, vp]
     L.tamoe_dispatch.restype = i32
     L.tamoe_dispatch.argtypes = [vp, vp, vp, i32, i64, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, sz, vp]
+    L.tamoe_dispatch_static.restype = i32
+    L.tamoe_dispatch_static.argtypes = [vp, vp, vp, i32, i64, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp]
     L.tamoe_combine.restype = i32
     L.tamoe_combine.argtypes = [vp, i64, vp, vp, i32, i64, i32, i32, vp, vp]
     L.tamoe_gate_bwd.restype = i32
@@ -294,6 +297,20 @@ def tamoe_dispatch(x, topk_idx, cap, N: int, P: int, send, slot, kept_expert, ex
         _dtype_code(x), S, d, N, P, k, _dev(send, None, "send"), _dev(slot, torch.int32, "slot"),
         _dev(kept_expert, torch.int32, "kept_expert"), _dev(expert_offset, torch.int32, "expert_offset"),
         _dev(send_count_dev, torch.int32, "send_count_dev"), wsp, wsn, _stream(stream)))
+
+
+def tamoe_dispatch_static(x, topk_idx, cap, N: int, P: int, send, slot, kept_expert, expert_offset, send_count_dev,
+                          stream=None) -> None:
+    """tamoe_dispatch with the library's built-in scratch instead of a workspace (allocates nothing)."""
+    S, d = x.shape
+    k = topk_idx.shape[1]
+    if send is not None and (send.dtype != x.dtype or send.numel() < S * k * d):
+        raise TamoeError(INVALID_ARG, "send must have the dtype of x and room for k*S rows")
+    _check(lib().tamoe_dispatch_static(
+        _dev(x, None, "x"), _dev(topk_idx, torch.int32, "topk_idx"), _dev(cap, torch.int32, "cap"),
+        _dtype_code(x), S, d, N, P, k, _dev(send, None, "send"), _dev(slot, torch.int32, "slot"),
+        _dev(kept_expert, torch.int32, "kept_expert"), _dev(expert_offset, torch.int32, "expert_offset"),
+        _dev(send_count_dev, torch.int32, "send_count_dev"), _stream(stream)))
 
 
 def tamoe_dispatch_padded(x, topk_idx, cap, N: int, P: int, C: int, send, slot, kept_expert, ws, stream=None) -> None:

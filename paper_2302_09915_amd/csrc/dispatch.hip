@@ -21,6 +21,7 @@
 // bytes per kept pair.  Chunks are laid out flat over the threads, so a wavefront always touches
 // 1 KiB of consecutive bytes, whatever d is.
 #include <algorithm>
+#include <mutex>
 
 #include "internal.h"
 #include "scan128.h"
@@ -265,14 +266,13 @@ __global__ __launch_bounds__(kThreads) void dispatch_pad_fill_kernel(const int32
 
 // Shared body of tamoe_dispatch (pad_C == 0: packed rows, expert after expert) and
 // tamoe_dispatch_padded (pad_C > 0: pad_C rows per expert, the unused ones zeroed).
+// tile_count: device scratch of k * count_tiles(S) * N ints; every entry is written by the count
+// kernel before it is read, so its content on entry does not matter.
 static int dispatch_impl(const char* fn, const void* x, const int32_t* topk_idx, const int32_t* cap, int dtype,
                          int64_t S, int d, int N, int P, int k, int pad_C, void* send, int32_t* slot,
-                         int32_t* kept_expert, int32_t* expert_offset, int32_t* send_count_dev, void* ws,
-                         size_t ws_bytes, void* stream) {
+                         int32_t* kept_expert, int32_t* expert_offset, int32_t* send_count_dev,
+                         int32_t* tile_count, void* stream) {
     int rc;
-    const Workspace lay = workspace_layout(S, N, k);
-    if (ws_bytes < lay.total)
-        return fail(TAMOE_WORKSPACE_TOO_SMALL, "%s: workspace has %zu bytes, %zu needed", fn, ws_bytes, lay.total);
     const int64_t n_ct = count_tiles(S);
     if ((int64_t)k * n_ct > (int64_t)1 << 30)
         return fail(TAMOE_UNSUPPORTED, "%s: too many count tiles (%lld)", fn, (long long)n_ct);
@@ -281,7 +281,6 @@ static int dispatch_impl(const char* fn, const void* x, const int32_t* topk_idx,
         return fail(TAMOE_UNSUPPORTED, "%s: x is too large for one launch", fn);
 
     hipStream_t st = static_cast<hipStream_t>(stream);
-    int32_t* tile_count = reinterpret_cast<int32_t*>(static_cast<char*>(ws) + lay.tile_count);
 
     if (n_ct > 0) {
         TraceScope tr("dispatch_count_kernel", st);
@@ -327,9 +326,75 @@ static int dispatch_impl(const char* fn, const void* x, const int32_t* topk_idx,
     return TAMOE_OK;
 }
 
+// The pair-count table inside a caller's workspace, or NULL (error recorded) if the workspace is too small.
+static int32_t* tile_count_in(const char* fn, void* ws, size_t ws_bytes, int64_t S, int N, int k) {
+    const Workspace lay = workspace_layout(S, N, k);
+    if (ws_bytes < lay.total) {
+        fail(TAMOE_WORKSPACE_TOO_SMALL, "%s: workspace has %zu bytes, %zu needed", fn, ws_bytes, lay.total);
+        return nullptr;
+    }
+    return reinterpret_cast<int32_t*>(static_cast<char*>(ws) + lay.tile_count);
+}
+
+// ---- scratch that lives in the library's own image (tamoe_dispatch_static) --------------------
+// One copy of this array exists on every device the library's code object is loaded on, at an address of
+// its own.  Host code must not use the array's name as a pointer: the per-device address is asked for
+// once (first call on that device, with that device current) and kept.
+constexpr int kStaticDevices = 64;
+static __device__ __align__(256) __attribute__((used)) unsigned char scratch[TAMOE_STATIC_SCRATCH_BYTES];
+static std::mutex g_scratch_lock;
+static void* g_scratch_ptr[kStaticDevices] = {};
+
+static int static_scratch(const char* fn, int32_t** out) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kStaticDevices)
+        return fail(TAMOE_HIP_ERROR, "%s: no current device (or device ordinal beyond %d)", fn, kStaticDevices - 1);
+    std::lock_guard<std::mutex> hold(g_scratch_lock);
+    if (g_scratch_ptr[dev] == nullptr) {
+        void* p = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || p == nullptr)
+            return fail(TAMOE_HIP_ERROR, "%s: hipGetSymbolAddress failed: %s", fn, hipGetErrorString(e));
+        g_scratch_ptr[dev] = p;
+    }
+    *out = static_cast<int32_t*>(g_scratch_ptr[dev]);
+    return TAMOE_OK;
+}
+
 }  // namespace tamoe
 
 using namespace tamoe;
+
+extern "C" int tamoe_dispatch_static(const void* x, const int32_t* topk_idx, const int32_t* cap, int dtype,
+                                     int64_t S, int d, int N, int P, int k, void* send, int32_t* slot,
+                                     int32_t* kept_expert, int32_t* expert_offset, int32_t* send_count_dev,
+                                     void* stream) {
+    const char* fn = "tamoe_dispatch_static";
+    clear_error();
+    int rc;
+    if ((rc = check_shape(fn, S, N, P, k)) != TAMOE_OK) return rc;
+    if ((rc = check_rows(fn, dtype, d)) != TAMOE_OK) return rc;
+    if ((rc = check_ptr(fn, "cap", cap, 4)) != TAMOE_OK) return rc;
+    if ((rc = check_ptr(fn, "kept_expert", kept_expert, 4)) != TAMOE_OK) return rc;
+    if ((rc = check_ptr(fn, "expert_offset", expert_offset, 4)) != TAMOE_OK) return rc;
+    if ((rc = check_ptr(fn, "send_count_dev", send_count_dev, 4)) != TAMOE_OK) return rc;
+    if (S > 0) {
+        if ((rc = check_ptr(fn, "x", x, 16)) != TAMOE_OK) return rc;
+        if ((rc = check_ptr(fn, "topk_idx", topk_idx, 4)) != TAMOE_OK) return rc;
+        if ((rc = check_ptr(fn, "send", send, 16)) != TAMOE_OK) return rc;
+        if ((rc = check_ptr(fn, "slot", slot, 4)) != TAMOE_OK) return rc;
+    }
+    const int64_t entries = (int64_t)k * count_tiles(S) * N;   // ints of scratch this shape needs
+    if (entries * (int64_t)sizeof(int32_t) > (int64_t)TAMOE_STATIC_SCRATCH_BYTES)
+        return fail(TAMOE_UNSUPPORTED,
+                    "%s: k * ceil(S/%d) * N = %lld pair counters exceed the %d of the built-in scratch; "
+                    "use tamoe_dispatch with a workspace",
+                    fn, kCountTile, (long long)entries, (int)(TAMOE_STATIC_SCRATCH_BYTES / sizeof(int32_t)));
+    int32_t* tile_count = nullptr;
+    if ((rc = static_scratch(fn, &tile_count)) != TAMOE_OK) return rc;
+    return dispatch_impl(fn, x, topk_idx, cap, dtype, S, d, N, P, k, 0, send, slot, kept_expert, expert_offset,
+                         send_count_dev, tile_count, stream);
+}
 
 extern "C" int tamoe_dispatch(const void* x, const int32_t* topk_idx, const int32_t* cap, int dtype, int64_t S,
                               int d, int N, int P, int k, void* send, int32_t* slot, int32_t* kept_expert,
@@ -351,8 +416,10 @@ extern "C" int tamoe_dispatch(const void* x, const int32_t* topk_idx, const int3
         if ((rc = check_ptr(fn, "send", send, 16)) != TAMOE_OK) return rc;
         if ((rc = check_ptr(fn, "slot", slot, 4)) != TAMOE_OK) return rc;
     }
+    int32_t* tile_count = tile_count_in(fn, ws, ws_bytes, S, N, k);
+    if (tile_count == nullptr) return TAMOE_WORKSPACE_TOO_SMALL;
     return dispatch_impl(fn, x, topk_idx, cap, dtype, S, d, N, P, k, 0, send, slot, kept_expert, expert_offset,
-                         send_count_dev, ws, ws_bytes, stream);
+                         send_count_dev, tile_count, stream);
 }
 
 extern "C" int tamoe_dispatch_padded(const void* x, const int32_t* topk_idx, const int32_t* cap, int dtype,
@@ -374,6 +441,8 @@ extern "C" int tamoe_dispatch_padded(const void* x, const int32_t* topk_idx, con
         if ((rc = check_ptr(fn, "topk_idx", topk_idx, 4)) != TAMOE_OK) return rc;
         if ((rc = check_ptr(fn, "slot", slot, 4)) != TAMOE_OK) return rc;
     }
+    int32_t* tile_count = tile_count_in(fn, ws, ws_bytes, S, N, k);
+    if (tile_count == nullptr) return TAMOE_WORKSPACE_TOO_SMALL;
     return dispatch_impl(fn, x, topk_idx, cap, dtype, S, d, N, P, k, C, send, slot, kept_expert, nullptr, nullptr,
-                         ws, ws_bytes, stream);
+                         tile_count, stream);
 }
