@@ -124,12 +124,20 @@ int tamoe_penalty(const double* c_hat, int N, int norm, double temperature, floa
  * "[[2,2],[2]]": the asymmetric 3-layer example).  Devices are numbered left to right.
  * level[i*P+j] = height of the lowest switch that joins devices i and j (1 = same device switch),
  * 0 on the diagonal: the labels tamoe_topo_pattern smooths over.  merge_asymmetric != 0 first merges
- * the tree (Section 4.2, last paragraph: "[[2,2],[2]]" becomes "[[2,2,2]]"): bottom-up, at every
- * list whose elements are all lists, an element with fewer members than the largest one hands its
- * members to the nearest largest sibling of the same height (the left one on a tie), repeatedly,
- * until nothing moves.  The paper shows the one example; the rule is this library's reading.
+ * the tree (Section 4.2, last paragraph: separate nodes join the close symmetric sub-trees so that the
+ * tree becomes symmetric; "[[2,2],[2]]" becomes "[[2,2,2]]").  The paper shows that one example; the
+ * rule is this library's reading: one pass from the leaves up; at a list whose elements are all lists,
+ * the elements with the most members are the full sub-trees, the smaller ones the separate nodes; each
+ * separate node, left to right, hands all its members to one full sub-tree of its own height: the
+ * one that has received the fewest members so far, the nearest of those, the left one at equal
+ * distance.  Sizes are taken once, before anything moves.  The result is symmetric when the separate
+ * nodes can be shared out equally ("[[2,2],[2,2],[2],[2]]" -> "[[2,2,2],[2,2,2]]"); otherwise it stays
+ * asymmetric with its layers kept ("[[2,2],[2,2],[2]]" -> "[[2,2],[2,2,2]]").  Device switches are
+ * never merged ("[3,1,2]" stays).  Devices keep the numbers of the tree as given, wherever the merge
+ * moves their switch.
  * level: room for max_P*max_P ints; *P_out = devices found; tree_out (may be NULL): the tree that
- * was labelled, as text.
+ * was labelled, as text; device_order (may be NULL, room for max_P ints): the device numbers in the
+ * order in which that tree lists them (0..P-1 unless the merge moved a switch past others).
  *
  * tamoe_ring_table: link q joins devices q and (q+1) mod P (inverse bandwidth beta_link[q] > 0,
  * latency alpha_link[q] >= 0 or alpha_link == NULL).  Other pairs hop over the devices between
@@ -146,7 +154,7 @@ int tamoe_penalty(const double* c_hat, int N, int norm, double temperature, floa
  * closed form, where it holds by symmetry of the table).
  */
 int tamoe_tree_levels(const char* tree, int merge_asymmetric, int max_P, int32_t* level, int* P_out,
-                      char* tree_out, size_t tree_out_len);
+                      char* tree_out, size_t tree_out_len, int32_t* device_order);
 int tamoe_ring_table(const double* beta_link, const double* alpha_link, int P, double self_beta,
                      double self_alpha, double* beta, double* alpha, int32_t* level);
 int tamoe_minmax_pattern(const double* alpha_row, const double* beta_row, int P, int N, int k, int64_t S,

@@ -71,7 +71,7 @@ def _load():
         "orc_slots_padded": (None, [c_vp, c_vp, c_i64, c_i32, c_i32, c_i32, c_vp, c_vp]),
         "orc_minmax_pattern": (c_dbl, [c_vp, c_vp, c_i32, c_i32, c_i32, c_i64, c_dbl, c_vp]),
         "orc_ring_table": (None, [c_vp, c_vp, c_i32, c_dbl, c_dbl, c_vp, c_vp, c_vp]),
-        "orc_tree_levels": (c_i32, [ctypes.c_char_p, c_i32, c_i32, c_vp, ctypes.c_char_p, c_i32]),
+        "orc_tree_levels": (c_i32, [ctypes.c_char_p, c_i32, c_i32, c_vp, ctypes.c_char_p, c_i32, c_vp]),
         "orc_regroup": (c_i64, [c_vp, c_i32, c_vp, c_i32, c_i32, c_i32, c_i32, c_vp, c_vp]),
     }
     for name, (res, args) in sig.items():
@@ -181,14 +181,18 @@ def ring_table(beta_link, alpha_link=None, self_beta: float = 1.0, self_alpha: f
     return beta, alpha, level
 
 
-def tree_levels(text: str, merge: bool, max_P: int = 1024):
-    """Nested-list tree -> (level[P,P], notation of the labelled tree).  Raises ValueError on bad text."""
+def tree_levels(text: str, merge: bool, max_P: int = 1024, want_order: bool = False):
+    """Nested-list tree -> (level[P,P] in the device numbers of the tree as given, notation of the
+    labelled tree[, device numbers in the order in which that tree lists them]).  Raises ValueError on
+    bad text."""
     level = np.empty((max_P * max_P,), dtype=np.int32)
+    order = np.empty((max_P,), dtype=np.int32)
     buf = ctypes.create_string_buffer(4096)
-    P = _load().orc_tree_levels(text.encode(), 1 if merge else 0, max_P, _p(level), buf, 4096)
+    P = _load().orc_tree_levels(text.encode(), 1 if merge else 0, max_P, _p(level), buf, 4096, _p(order))
     if P < 0:
         raise ValueError(f"orc_tree_levels({text!r}) failed with {P}")
-    return level[:P * P].reshape(P, P).copy(), buf.value.decode()
+    out = (level[:P * P].reshape(P, P).copy(), buf.value.decode())
+    return out + (order[:P].copy(),) if want_order else out
 
 
 def capacity(c_hat, k: int, S: int, cf: float, mode: int) -> np.ndarray:

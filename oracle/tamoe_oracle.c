@@ -402,6 +402,8 @@ void orc_ring_table(const double *beta_link, const double *alpha_link, int P, do
 #define ORC_MAX_NODES 4096
 typedef struct {
     int n_dev[ORC_MAX_NODES];   /* > 0: a switch with that many devices; 0: a list */
+    int base[ORC_MAX_NODES];    /* device switch: number of its first device in the tree as given */
+    int seen;                   /* devices read so far */
     int first[ORC_MAX_NODES];   /* first child of a list, -1 if none */
     int next[ORC_MAX_NODES];    /* next sibling, -1 at the end */
     int used;
@@ -433,6 +435,8 @@ static int parse_element(orc_tree *t)
         if (v <= 0 || v >= 100000)
             t->bad = 1;
         t->n_dev[me] = (int)v;
+        t->base[me] = t->seen;
+        t->seen += (int)v;
         return me;
     }
     if (*t->s != '[') {
@@ -486,49 +490,74 @@ static int child_count(const orc_tree *t, int v)
 }
 
 /*
- * Merge of an asymmetric tree (Section 4.2, last paragraph: separate nodes are merged into the
- * close symmetric sub-tree; [[2,2],[2]] becomes [[2,2,2]]).  Reading: bottom-up, at every list
- * whose elements are all lists, an element with fewer members than the largest of its siblings
- * hands its members to the nearest sibling (the left one on a tie) that has the largest member
- * count and the same height, and disappears; this is repeated, sub-trees that took members in
- * included, until the member counts agree (or no sibling qualifies), so that merging the outcome
- * again changes nothing.
+ * Merge of an asymmetric tree (Section 4.2, last paragraph: for fairness among the experts the
+ * separate nodes are merged into the close symmetric sub-trees; [[2,2],[2]] becomes [[2,2,2]]).
+ * The paper gives that one example and the aim: a symmetric tree, on which the second constraint of
+ * Section 4.1 (every expert receives k*S/E rows) holds for the closed-form pattern again.
+ * Reading taken here, one pass from the leaves up; at a list whose elements are all lists:
+ *   - the reference size is the largest member count among the elements as they stand when the list
+ *     is reached; elements of that size are the full sub-trees, smaller ones the separate nodes;
+ *   - the separate nodes are taken from left to right; each hands all its members to one full
+ *     sub-tree of its own height and disappears.  Of the candidates it takes the one that has been
+ *     given the fewest members so far, then the one nearest to it in the list, then the left one;
+ *   - nothing is looked at twice: the reference and the set of full sub-trees stay what they were.
+ * Spreading the members evenly makes the list symmetric whenever the separate nodes can be shared
+ * out equally; when they cannot ([[2,2],[2,2],[2]] -> [[2,2],[2,2,2]]) the tree stays asymmetric and
+ * keeps its layers rather than collapsing into one switch.
  */
-static int merge_once(orc_tree *t, int v)
+typedef struct {
+    int taken, dist, pos;                 /* order of preference among the full sub-trees */
+} orc_merge_key;
+
+static int key_before(orc_merge_key a, orc_merge_key b)
 {
-    int kids[512], size0[512], gone[512];
-    int n = 0, most = 0, moved = 0;
+    if (a.taken != b.taken)
+        return a.taken < b.taken;
+    if (a.dist != b.dist)
+        return a.dist < b.dist;
+    return a.pos < b.pos;
+}
+
+static void merge_list(orc_tree *t, int v)
+{
+    int kids[512], size0[512], high[512], taken[512], gone[512];
+    int n = 0, ref = 0;
     for (int c = t->first[v]; c >= 0; c = t->next[c]) {
         if (t->n_dev[c] > 0 || n >= 512)
-            return 0;                     /* a device switch among the elements: nothing to merge */
+            return;                       /* a device switch among the elements: nothing to merge */
         kids[n++] = c;
     }
     for (int i = 0; i < n; ++i) {
         size0[i] = child_count(t, kids[i]);
+        high[i] = tree_height(t, kids[i]);
+        taken[i] = 0;
         gone[i] = 0;
-        if (size0[i] > most)
-            most = size0[i];
+        if (size0[i] > ref)
+            ref = size0[i];
     }
     for (int i = 0; i < n; ++i) {
-        if (size0[i] == most)
+        if (size0[i] == ref)
             continue;
         int target = -1;
-        for (int dist = 1; dist < n && target < 0; ++dist) {
-            int l = i - dist, r = i + dist;
-            if (l >= 0 && size0[l] == most && tree_height(t, kids[l]) == tree_height(t, kids[i]))
-                target = l;
-            else if (r < n && size0[r] == most && tree_height(t, kids[r]) == tree_height(t, kids[i]))
-                target = r;
+        orc_merge_key best = {0, 0, 0};
+        for (int j = 0; j < n; ++j) {
+            if (size0[j] != ref || high[j] != high[i])
+                continue;
+            orc_merge_key key = {taken[j], j > i ? j - i : i - j, j};
+            if (target < 0 || key_before(key, best)) {
+                target = j;
+                best = key;
+            }
         }
         if (target < 0)
             continue;
         int tail = t->first[kids[target]];
         while (t->next[tail] >= 0)
             tail = t->next[tail];
-        t->next[tail] = t->first[kids[i]];     /* members move to the end of the target's list */
+        t->next[tail] = t->first[kids[i]];     /* members go to the end of the target's list */
         t->first[kids[i]] = -1;
+        taken[target] += size0[i];
         gone[i] = 1;
-        moved = 1;
     }
     int last = -1;
     t->first[v] = -1;
@@ -542,17 +571,15 @@ static int merge_once(orc_tree *t, int v)
         t->next[kids[i]] = -1;
         last = kids[i];
     }
-    return moved;
 }
 
 static void merge_tree(orc_tree *t, int v)
 {
     if (t->n_dev[v] > 0)
         return;
-    do {                                  /* a sub-tree that took members in is looked at again */
-        for (int c = t->first[v]; c >= 0; c = t->next[c])
-            merge_tree(t, c);
-    } while (merge_once(t, v));
+    for (int c = t->first[v]; c >= 0; c = t->next[c])
+        merge_tree(t, c);
+    merge_list(t, v);
 }
 
 static int count_devices(const orc_tree *t, int v)
@@ -565,22 +592,33 @@ static int count_devices(const orc_tree *t, int v)
     return n;
 }
 
-/* level labels of all pairs with both devices below v; devices of v are base .. base+count-1 */
-static void label_pairs(const orc_tree *t, int v, int base, int P, int32_t *level)
+/* numbers (as given) of the devices below v, left to right in the tree as it stands; returns how many */
+static int devices_below(const orc_tree *t, int v, int32_t *out)
+{
+    if (t->n_dev[v] > 0) {
+        for (int q = 0; q < t->n_dev[v]; ++q)
+            out[q] = t->base[v] + q;
+        return t->n_dev[v];
+    }
+    int n = 0;
+    for (int c = t->first[v]; c >= 0; c = t->next[c])
+        n += devices_below(t, c, out + n);
+    return n;
+}
+
+/* level labels of all pairs with both devices below v; dev: room for the device numbers below v */
+static void label_pairs(const orc_tree *t, int v, int P, int32_t *level, int32_t *dev)
 {
     int h = tree_height(t, v);
-    int n = count_devices(t, v);
+    int n = devices_below(t, v, dev);
     /* every pair below v gets v's height first; deeper switches overwrite their own pairs */
-    for (int i = base; i < base + n; ++i)
-        for (int j = base; j < base + n; ++j)
-            level[i * P + j] = i == j ? 0 : h;
+    for (int a = 0; a < n; ++a)
+        for (int b = 0; b < n; ++b)
+            level[dev[a] * P + dev[b]] = a == b ? 0 : h;
     if (t->n_dev[v] > 0)
         return;
-    int b = base;
-    for (int c = t->first[v]; c >= 0; c = t->next[c]) {
-        label_pairs(t, c, b, P, level);
-        b += count_devices(t, c);
-    }
+    for (int c = t->first[v]; c >= 0; c = t->next[c])
+        label_pairs(t, c, P, level, dev);
 }
 
 static int print_tree(const orc_tree *t, int v, char *out, int len, int pos)
@@ -610,15 +648,19 @@ static int print_tree(const orc_tree *t, int v, char *out, int len, int pos)
 
 /*
  * Level table of a tree topology: level[i][j] = height of the lowest switch that joins devices i
- * and j (1: the same device switch, 2: one layer up, ...), 0 on the diagonal.  With merge != 0 the
- * tree is merged first (see merge_tree).  `text_out` (may be NULL) receives the notation of the
- * tree that was labelled.  Returns the number of devices P, -1 on a syntax error, -2 if P > max_P.
+ * and j (1: the same device switch, 2: one layer up, ...), 0 on the diagonal.  Devices keep the
+ * numbers they have in the tree as given (left to right), also when the merge (merge != 0, see
+ * merge_list) moves their switch elsewhere.  `text_out` (may be NULL) receives the notation of the
+ * tree that was labelled and `order_out` (may be NULL, room for max_P) the device numbers in the
+ * order in which that tree lists them.  Returns the number of devices P, -1 on a syntax error,
+ * -2 if P > max_P.
  */
 int orc_tree_levels(const char *text, int merge, int max_P, int32_t *level, char *text_out,
-                    int text_len)
+                    int text_len, int32_t *order_out)
 {
     orc_tree *t = (orc_tree *)malloc(sizeof(orc_tree));
     t->used = 0;
+    t->seen = 0;
     t->s = text;
     t->bad = 0;
     int root = parse_element(t);
@@ -634,7 +676,11 @@ int orc_tree_levels(const char *text, int merge, int max_P, int32_t *level, char
         free(t);
         return -2;
     }
-    label_pairs(t, root, 0, P, level);
+    int32_t *dev = (int32_t *)malloc(sizeof(int32_t) * (size_t)P);
+    label_pairs(t, root, P, level, dev);
+    if (order_out != NULL)
+        devices_below(t, root, order_out);
+    free(dev);
     if (text_out != NULL && text_len > 0) {
         int pos = print_tree(t, root, text_out, text_len, 0);
         text_out[pos] = '\0';

@@ -92,7 +92,7 @@ def lib() -> ctypes.CDLL:
     L.tamoe_regroup.restype = i32
     L.tamoe_regroup.argtypes = [vp, vp, i32, i32, i32, i32, i64, i32, vp, vp, vp, sz, vp]
     L.tamoe_tree_levels.restype = i32
-    L.tamoe_tree_levels.argtypes = [ctypes.c_char_p, i32, i32, vp, ctypes.POINTER(ctypes.c_int), ctypes.c_char_p, sz]
+    L.tamoe_tree_levels.argtypes = [ctypes.c_char_p, i32, i32, vp, ctypes.POINTER(ctypes.c_int), ctypes.c_char_p, sz, vp]
     L.tamoe_ring_table.restype = i32
     L.tamoe_ring_table.argtypes = [vp, vp, i32, dbl, dbl, vp, vp, vp]
     L.tamoe_minmax_pattern.restype = i32
@@ -202,15 +202,17 @@ def _hp(a):
     return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
 
 
-def tamoe_tree_levels(tree: str, merge_asymmetric: bool, max_P: int = 1024):
-    """Host.  Nested-list text -> (level i32[P,P], text of the labelled tree)."""
+def tamoe_tree_levels(tree: str, merge_asymmetric: bool, max_P: int = 1024, want_order: bool = False):
+    """Host.  Nested-list text -> (level i32[P,P], text of the labelled tree[, device order i32[P]])."""
     level = np.empty(max_P * max_P, dtype=np.int32)
+    order = np.empty(max_P, dtype=np.int32)
     P = ctypes.c_int(0)
     buf = ctypes.create_string_buffer(max(4096, 4 * len(tree) + 16))
     _check(lib().tamoe_tree_levels(tree.encode(), 1 if merge_asymmetric else 0, max_P, _hp(level), ctypes.byref(P),
-                                   buf, len(buf)))
+                                   buf, len(buf), _hp(order)))
     n = P.value
-    return level[:n * n].reshape(n, n).copy(), buf.value.decode()
+    out = (level[:n * n].reshape(n, n).copy(), buf.value.decode())
+    return out + (order[:n].copy(),) if want_order else out
 
 
 def tamoe_ring_table(beta_link, alpha_link=None, self_beta: float = 1.0, self_alpha: float = 0.0):

@@ -3,6 +3,7 @@
 #include <cmath>
 #include <cstdio>
 #include <cstring>
+#include <map>
 #include <vector>
 
 #include "internal.h"
@@ -235,20 +236,28 @@ extern "C" int tamoe_topo_pattern(const double* beta, const int32_t* level, int 
     // Row `rank` of the hierarchical matrix.
     std::vector<double> row(beta + (size_t)rank * P, beta + (size_t)(rank + 1) * P);
     if (level != nullptr) {
-        int n_levels = 0;
-        for (int q = 0; q < P * P; ++q) n_levels = level[q] + 1 > n_levels ? level[q] + 1 : n_levels;
-        std::vector<double> pair_sum(n_levels, 0.0), self_sum(n_levels, 0.0);
-        std::vector<int64_t> pair_cnt(n_levels, 0), self_cnt(n_levels, 0);
+        // labels are arbitrary non-negative integers: sums are kept per label that occurs
+        struct LevelSum {
+            double pair_sum = 0.0, self_sum = 0.0;
+            int64_t pair_cnt = 0, self_cnt = 0;
+        };
+        std::map<int32_t, LevelSum> by_level;
         for (int a = 0; a < P; ++a) {
             for (int b = a; b < P; ++b) {
-                const int l = level[a * P + b];
-                if (a == b) { self_sum[l] += beta[a * P + b]; self_cnt[l] += 1; }
-                else        { pair_sum[l] += beta[a * P + b]; pair_cnt[l] += 1; }
+                LevelSum& s = by_level[level[a * P + b]];
+                if (a == b) { s.self_sum += beta[a * P + b]; s.self_cnt += 1; }
+                else        { s.pair_sum += beta[a * P + b]; s.pair_cnt += 1; }
             }
         }
         for (int j = 0; j < P; ++j) {
-            const int l = level[rank * P + j];
-            row[j] = pair_cnt[l] > 0 ? pair_sum[l] / (double)pair_cnt[l] : self_sum[l] / (double)self_cnt[l];
+            // level[rank][j] and level[j][rank] may differ in a table that is not symmetric; the
+            // upper triangle was summed, the label of the row is looked up
+            const auto it = by_level.find(level[rank * P + j]);
+            if (it == by_level.end() || (it->second.pair_cnt == 0 && it->second.self_cnt == 0))
+                return fail(TAMOE_INVALID_ARG, "%s: level[%d][%d] = %d labels no pair i <= j", fn, rank, j,
+                            level[rank * P + j]);
+            const LevelSum& s = it->second;
+            row[j] = s.pair_cnt > 0 ? s.pair_sum / (double)s.pair_cnt : s.self_sum / (double)s.self_cnt;
         }
     }
 

@@ -4,6 +4,7 @@
 // produce the tables that tamoe_topo_pattern consumes; nothing here touches the GPU.
 #include <algorithm>
 #include <cmath>
+#include <cstdint>
 #include <cstring>
 #include <numeric>
 #include <string>
@@ -17,12 +18,14 @@ namespace {
 // ---- trees -------------------------------------------------------------------------------------
 struct Node {
     int devices = 0;          // > 0: a switch with that many devices and no sub-switches
+    int first_device = 0;     // device switch: number of its first device in the tree as given
     std::vector<Node> kids;   // otherwise: the elements of the list
 };
 
 struct Parser {
     const char* p;
     bool ok = true;
+    int devices_seen = 0;
     void blanks() {
         while (*p == ' ' || *p == '\t') ++p;
     }
@@ -38,6 +41,8 @@ struct Parser {
             }
             if (v <= 0) ok = false;
             n.devices = (int)v;
+            n.first_device = devices_seen;
+            devices_seen += (int)v;
             return n;
         }
         if (*p != '[') {
@@ -75,63 +80,76 @@ int device_count(const Node& n) {
     return total;
 }
 
-// One pass of the merge at `n`: every element that is smaller than the largest one joins the
-// nearest largest element of its own height.  Returns whether anything moved.
-bool absorb_small_elements(Node& n) {
+// Merge at one list (Section 4.2, last paragraph; the paper shows [[2,2],[2]] -> [[2,2,2]] and names
+// the aim, a symmetric tree).  The elements with the most members are the full sub-trees, the smaller
+// ones the separate nodes.  Every separate node, left to right, empties itself into a full sub-tree
+// of its own height: the least loaded one (members received so far), the nearest of those, the left
+// one at equal distance.  The sizes are taken once, before anything moves.
+void absorb_separate_nodes(Node& n) {
     const size_t cnt = n.kids.size();
     size_t largest = 0;
     for (const Node& c : n.kids) {
-        if (c.devices > 0) return false;
+        if (c.devices > 0) return;        // device switches are never merged
         largest = std::max(largest, c.kids.size());
     }
-    std::vector<size_t> size(cnt);
-    std::vector<int> h(cnt);
+    std::vector<size_t> size(cnt), received(cnt, 0);
+    std::vector<int> h(cnt), into(cnt, -1);
     for (size_t i = 0; i < cnt; ++i) {
         size[i] = n.kids[i].kids.size();
         h[i] = height(n.kids[i]);
     }
-    std::vector<int> into(cnt, -1);
+    bool moved = false;
     for (size_t i = 0; i < cnt; ++i) {
         if (size[i] == largest) continue;
+        // lightest load among the full sub-trees this node may join
+        size_t lightest = SIZE_MAX;
+        for (size_t j = 0; j < cnt; ++j)
+            if (size[j] == largest && h[j] == h[i]) lightest = std::min(lightest, received[j]);
+        if (lightest == SIZE_MAX) continue;  // no full sub-tree of this height: the node stays
+        // walk outwards from the node, left before right, to the first one that carries that load
         for (size_t dist = 1; dist < cnt && into[i] < 0; ++dist) {
-            if (i >= dist && size[i - dist] == largest && h[i - dist] == h[i])
-                into[i] = (int)(i - dist);
-            else if (i + dist < cnt && size[i + dist] == largest && h[i + dist] == h[i])
-                into[i] = (int)(i + dist);
+            const size_t l = i - dist, r = i + dist;   // l wraps around below zero and then fails l < cnt
+            if (l < cnt && size[l] == largest && h[l] == h[i] && received[l] == lightest)
+                into[i] = (int)l;
+            else if (r < cnt && size[r] == largest && h[r] == h[i] && received[r] == lightest)
+                into[i] = (int)r;
         }
+        received[(size_t)into[i]] += size[i];
+        moved = true;
     }
-    bool moved = false;
+    if (!moved) return;
+    // members move in the order the separate nodes were visited; the emptied nodes disappear
     for (size_t i = 0; i < cnt; ++i) {
         if (into[i] < 0) continue;
         Node& dst = n.kids[(size_t)into[i]];
         for (Node& m : n.kids[i].kids) dst.kids.push_back(std::move(m));
         n.kids[i].kids.clear();
-        moved = true;
     }
-    if (moved) {
-        std::vector<Node> rest;
-        for (size_t i = 0; i < cnt; ++i)
-            if (into[i] < 0) rest.push_back(std::move(n.kids[i]));
-        n.kids = std::move(rest);
-    }
-    return moved;
+    std::vector<Node> rest;
+    for (size_t i = 0; i < cnt; ++i)
+        if (into[i] < 0) rest.push_back(std::move(n.kids[i]));
+    n.kids = std::move(rest);
 }
 
+// One pass from the leaves up; a list that has taken members in is not looked at again.
 void merge(Node& n) {
     if (n.devices > 0) return;
-    do {
-        for (Node& c : n.kids) merge(c);
-    } while (absorb_small_elements(n));
+    for (Node& c : n.kids) merge(c);
+    absorb_separate_nodes(n);
 }
 
-// chain[dev] = heights of the switches above device `dev`, lowest first; id[dev] = their numbers
+// chain[dev] = (number, height) of the switches above device `dev` (numbered as in the tree as
+// given), lowest first; order: the device numbers from left to right in the tree as it stands
 void collect_chains(const Node& n, int& next_id, std::vector<std::pair<int, int>>& above,
-                    std::vector<std::vector<std::pair<int, int>>>& chain) {
+                    std::vector<std::vector<std::pair<int, int>>>& chain, std::vector<int>& order) {
     above.push_back({next_id++, height(n)});
     if (n.devices > 0) {
-        for (int q = 0; q < n.devices; ++q) chain.emplace_back(above.rbegin(), above.rend());
+        for (int q = 0; q < n.devices; ++q) {
+            chain[(size_t)(n.first_device + q)].assign(above.rbegin(), above.rend());
+            order.push_back(n.first_device + q);
+        }
     } else {
-        for (const Node& c : n.kids) collect_chains(c, next_id, above, chain);
+        for (const Node& c : n.kids) collect_chains(c, next_id, above, chain, order);
     }
     above.pop_back();
 }
@@ -155,7 +173,7 @@ void print(const Node& n, std::string& out) {
 using namespace tamoe;
 
 extern "C" int tamoe_tree_levels(const char* tree, int merge_asymmetric, int max_P, int32_t* level, int* P_out,
-                                 char* tree_out, size_t tree_out_len) {
+                                 char* tree_out, size_t tree_out_len, int32_t* device_order) {
     const char* fn = "tamoe_tree_levels";
     clear_error();
     if (tree == nullptr || level == nullptr || P_out == nullptr) return fail(TAMOE_INVALID_ARG, "%s: NULL pointer", fn);
@@ -169,10 +187,13 @@ extern "C" int tamoe_tree_levels(const char* tree, int merge_asymmetric, int max
     if (merge_asymmetric) merge(root);
     const int P = device_count(root);
     if (P > max_P) return fail(TAMOE_INVALID_ARG, "%s: the tree has %d devices, the table has room for %d", fn, P, max_P);
-    std::vector<std::vector<std::pair<int, int>>> chain;
+    std::vector<std::vector<std::pair<int, int>>> chain((size_t)P);
     std::vector<std::pair<int, int>> above;
+    std::vector<int> order;
     int next_id = 0;
-    collect_chains(root, next_id, above, chain);
+    collect_chains(root, next_id, above, chain, order);
+    if (device_order != nullptr)
+        for (int i = 0; i < P; ++i) device_order[i] = order[(size_t)i];
     for (int i = 0; i < P; ++i) {
         for (int j = 0; j < P; ++j) {
             int lv = 0;

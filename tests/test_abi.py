@@ -103,6 +103,10 @@ def test_topo_pattern_smooths_noisy_tables_like_the_oracle(T, oracle):
         np.testing.assert_allclose(c_hat, oc, rtol=1e-12)
         np.testing.assert_allclose(pen, op, rtol=1e-6)
         np.testing.assert_array_equal(cap, ocap)
+    # labels are names, not sizes: huge ones cost nothing and give the same pattern
+    big = np.where(level == 0, 7, np.where(level == 1, 2_000_000_000, 1_999_999_999)).astype(np.int32)
+    c_big, _, _ = T.tamoe_topo_pattern(noisy, big, 16, 32, 9, 2, 4096, 1.25, 1)
+    np.testing.assert_allclose(c_big, oc, rtol=1e-12)
     # without a level table the raw row is used
     c_hat, _, _ = T.tamoe_topo_pattern(noisy, None, 16, 16, 3, 1, 1000, 1.0, 0)
     np.testing.assert_allclose(c_hat, oracle.target_pattern(noisy, 16, 3, 1, 1000), rtol=1e-13)

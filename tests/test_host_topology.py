@@ -24,16 +24,19 @@ def T():
 
 TREES = ["8", "[4,4]", "[2,2,2,2]", "[[2,2],[2,2]]", "[[4,4,4],[4,4,4]]", "[[[2,2],[2,2]],[[2,2],[2,2]]]", "[3,1,2]",
          "[[2,2],[2]]", "[[2,2],[2,2],[2]]", "[[2],[2,2,2],[2,2,2],[2]]", "[[[2,2],[2]],[[2,2],[2,2]]]", "[2,[3]]",
-         " [ 2 , [ 3 ] ] ", "[[8,8,8,8,8,8,8,8]]", "[[1],[1,1],[1,1,1]]", "[[2,[2]],[2]]"]
+         " [ 2 , [ 3 ] ] ", "[[8,8,8,8,8,8,8,8]]", "[[1],[1,1],[1,1,1]]", "[[2,[2]],[2]]", "[[2,2],[2,2],[2],[2]]",
+         "[[[2,2],[2,2]],[[2,2]]]", "[[2,2,2],[2],[2,2,2],[2],[2]]", "[[[2,2],[2,2]],[2]]", "[[4,4],[4]]",
+         "[[3],[3,3],[3],[3,3],[3],[3,3],[3]]", "[[[2],[2,2]],[[2,2],[2]],[[2]]]"]
 
 
 @pytest.mark.parametrize("text", TREES)
 @pytest.mark.parametrize("merge", [False, True])
 def test_tree_levels_match_oracle(T, oracle, text, merge):
-    lv, shown = T.tamoe_tree_levels(text, merge)
-    ref_lv, ref_shown = oracle.tree_levels(text, merge)
+    lv, shown, order = T.tamoe_tree_levels(text, merge, want_order=True)
+    ref_lv, ref_shown, ref_order = oracle.tree_levels(text, merge, want_order=True)
     assert shown == ref_shown
     np.testing.assert_array_equal(lv, ref_lv)
+    np.testing.assert_array_equal(order, ref_order)
 
 
 def test_tree_levels_feed_the_pattern(T, oracle):

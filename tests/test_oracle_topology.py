@@ -190,9 +190,17 @@ def test_tree_merge_golden_examples(oracle):
         np.testing.assert_array_equal(lv0, _levels_by_lists(ast.literal_eval(given)))
 
 
+def _symmetric(n):
+    """Every list's elements are alike, all the way down: the paper's symmetric tree."""
+    if isinstance(n, int):
+        return True
+    return all(_symmetric(c) for c in n) and len({repr(c) for c in n}) == 1
+
+
 @pytest.mark.parametrize("text", ["8", "[4,4]", "[2,2,2,2]", "[[2,2],[2,2]]", "[[4,4,4],[4,4,4]]", "[[[2,2],[2,2]],[[2,2],[2,2]]]",
                                   "[3,1,2]", "[[2,2],[2]]", "[[2,2],[2,2],[2]]", "[[2],[2,2,2],[2,2,2],[2]]",
-                                  "[[[2,2],[2]],[[2,2],[2,2]]]", " [ 2 , [ 3 ] ] "])
+                                  "[[[2,2],[2]],[[2,2],[2,2]]]", " [ 2 , [ 3 ] ] ", "[[2,2],[2,2],[2],[2]]",
+                                  "[[[2,2],[2,2]],[[2,2]]]", "[[2,2,2],[2],[2,2,2],[2],[2]]"])
 def test_tree_levels_invariants(oracle, text):
     plain = ast.literal_eval(text.strip())
     lv, shown = oracle.tree_levels(text, False)
@@ -200,19 +208,82 @@ def test_tree_levels_invariants(oracle, text):
     assert shown == text.replace(" ", "")
     np.testing.assert_array_equal(lv, lv.T)
     assert (np.diag(lv) == 0).all()
-    merged_lv, merged = oracle.tree_levels(text, True)
+    merged_lv, merged, order = oracle.tree_levels(text, True, want_order=True)
     assert merged_lv.shape == lv.shape                                   # devices are neither lost nor made
-    np.testing.assert_array_equal(merged_lv, _levels_by_lists(ast.literal_eval(merged)))
-    assert oracle.tree_levels(merged, True)[1] == merged                 # merging again changes nothing
+    tree = ast.literal_eval(merged)
+    # devices keep their numbers: the merged tree, read left to right, lists them in `order`
+    np.testing.assert_array_equal(np.sort(order), np.arange(lv.shape[0]))
+    np.testing.assert_array_equal(merged_lv[np.ix_(order, order)], _levels_by_lists(tree))
     assert (merged_lv <= lv).all()                                       # a merge only brings devices closer
-
-    def symmetric(n):
-        if isinstance(n, int):
-            return True
-        return all(symmetric(c) for c in n) and len({repr(c) for c in n}) == 1
-
-    if symmetric(plain):
+    np.testing.assert_array_equal(oracle.tree_levels(text, False, want_order=True)[2], np.arange(lv.shape[0]))
+    if _symmetric(plain):
         assert merged == shown                                           # symmetric trees are left alone
+    if _symmetric(tree):
+        assert oracle.tree_levels(merged, True)[1] == merged             # nothing left to merge
+
+
+# The merge rule is this build's reading of one example and one stated aim (Section 4.2, last paragraph:
+# a symmetric tree).  Outcomes worked by hand from the rule as the oracle's comment states it (full
+# sub-trees = the largest siblings; separate nodes, left to right, go to the least loaded, then nearest,
+# then left full sub-tree of their height; one pass from the leaves up).
+MERGE_BY_HAND = [
+    # given, merged, symmetric afterwards, device numbers in the order of the merged tree (None: unchanged)
+    ("[[2,2],[2]]", "[[2,2,2]]", True, None),                            # the paper's example
+    ("[[4,4],[4]]", "[[4,4,4]]", True, None),
+    ("[[2,2],[2,2],[2],[2]]", "[[2,2,2],[2,2,2]]", True,                 # shared out evenly: the first separate node
+     [0, 1, 2, 3, 10, 11, 4, 5, 6, 7, 8, 9]),                            # goes to its neighbour, the second to the other
+    ("[[2],[2,2,2],[2,2,2],[2]]", "[[2,2,2,2],[2,2,2,2]]", True,
+     [2, 3, 4, 5, 6, 7, 0, 1, 8, 9, 10, 11, 12, 13, 14, 15]),            # members join at the end of the list
+    ("[[[2,2],[2,2]],[[2,2]]]", "[[[2,2],[2,2],[2,2]]]", True, None),    # a separate node one layer up
+    ("[[2,2,2],[2],[2,2,2],[2],[2]]", "[[2,2,2,2],[2,2,2,2,2]]", False,  # 3 nodes over 2 sub-trees: left (tie),
+     None),                                                              # right (less loaded), right (nearer)
+    ("[[2,2],[2,2],[2]]", "[[2,2],[2,2,2]]", False, None),               # cannot be shared out: layers are kept
+    ("[[[2,2],[2]],[[2,2],[2,2]]]", "[[[2,2],[2,2],[2,2,2]]]", False,    # inner merge first, then one layer up
+     [6, 7, 8, 9, 10, 11, 12, 13, 0, 1, 2, 3, 4, 5]),
+    ("[3,1,2]", "[3,1,2]", False, None),                                 # device switches are never merged
+    ("[[[2,2],[2,2]],[2]]", "[[[2,2],[2,2]],[2]]", False, None),         # no full sub-tree of the node's height
+]
+
+
+@pytest.mark.parametrize("given,merged,sym,order", MERGE_BY_HAND)
+def test_tree_merge_rule_by_hand(oracle, given, merged, sym, order):
+    lv, text, got_order = oracle.tree_levels(given, True, want_order=True)
+    assert text == merged
+    assert _symmetric(ast.literal_eval(text)) == sym
+    order = np.arange(lv.shape[0]) if order is None else np.array(order)
+    np.testing.assert_array_equal(got_order, order)
+    np.testing.assert_array_equal(lv[np.ix_(order, order)], _levels_by_lists(ast.literal_eval(merged)))
+
+
+@pytest.mark.parametrize("given,merged,sym,order", MERGE_BY_HAND)
+def test_tree_merge_restores_the_receive_constraint_where_it_makes_the_tree_symmetric(oracle, given, merged, sym, order):
+    """What the merge is for (Section 4.2: optimise "as the symmetric structure"): on a symmetric tree
+    every device sees the same set of link levels, so the closed-form pattern of all senders together
+    gives every expert k*S/E rows (the second constraint of Section 4.1).  Where the rule cannot make
+    the tree symmetric the constraint stays violated, and the hierarchy is kept instead of being
+    flattened into one switch."""
+    lv, text = oracle.tree_levels(given, True)
+    P = lv.shape[0]
+    E, k, S = 2, 2, 1000
+    N = P * E
+    per_level = np.array([1.0, 1.0, 3.0, 10.0, 31.0])                    # self, same switch, one up, ...
+    beta_hat = per_level[lv]
+    c = np.stack([oracle.target_pattern(beta_hat, N, i, k, S) for i in range(P)])
+    np.testing.assert_allclose(c.sum(axis=1), k * S, rtol=1e-12)         # first constraint: always
+    col = c.sum(axis=0)
+    seen = {tuple(sorted(row)) for row in lv.tolist()}
+    if sym:
+        assert len(seen) == 1
+        np.testing.assert_allclose(col, k * S * P / N, rtol=1e-12)
+    else:
+        assert len(seen) > 1
+        assert np.abs(col / (k * S * P / N) - 1.0).max() > 1e-3
+    if given == "[[2,2],[2,2],[2]]":
+        assert lv.max() == 3                                             # still three layers, not one flat switch
+        lv0, _ = oracle.tree_levels(given, False)
+        c0 = np.stack([oracle.target_pattern(per_level[lv0], N, i, k, S) for i in range(P)])
+        spread = lambda v: v.max() / v.min()
+        assert spread(col) < spread(c0.sum(axis=0))                      # and the isolated node is better served
 
 
 def test_tree_two_tier_levels_give_the_generator_table(oracle):
