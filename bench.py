@@ -2,17 +2,23 @@
 """Benchmark of the TA-MoE hot path on one MI355X.
 
 A step is one pass of the whole path over one batch of synthetic tokens that are already in
-HBM: tamoe_gate -> tamoe_aux_loss -> tamoe_dispatch -> tamoe_combine (identity expert: the
-combine reads the send buffer).  The metric is routed tokens per second.
+HBM: tamoe_gate_dispatch (gate, loss, slots, scatter) -> tamoe_combine (identity expert: the
+combine reads the send buffer); with --path separate: tamoe_gate -> tamoe_aux_loss ->
+tamoe_dispatch -> tamoe_combine.  The metric is routed tokens per second.
 
   python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload large] [--cap-mode 0]
 
+The timed region is `--blocks` blocks of K steps, each between two device synchronisations;
+`value` and `ms_per_step` are those of the median block (min and max beside them).
 Prints one JSON line.  Besides the contract fields it carries
   roofline     achieved algorithmic HBM GB/s of the longest-running kernel against 8 TB/s, from
                HIP events recorded around that kernel's launches inside the timed region;
   kernels      the same for every kernel of the step, from an untimed pass with events around
                every launch (two event records per launch cost ~3 us of GPU time each, so only
                the dominant kernel is bracketed while `value` is being measured);
+  scatter      the row scatter twice: behind the gate (as in the step: part of x still sits in the
+               last-level cache) and from HBM alone (tamoe_dispatch called on its own);
+  other_workloads  ms per step of the paper-sized configurations, eager and replayed from a HIP graph;
   cpu_baseline the CPU oracle timed on the host cores on a bounded sample of the workload.
 """
 from __future__ import annotations
@@ -37,6 +43,7 @@ def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--blocks", type=int, default=5, help="timed blocks of --steps steps; the median block is reported")
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="large",
                     help="tiny, small, gpt_moe, skewed, large (the measured configurations) or one of the paper's own "
@@ -46,7 +53,8 @@ def parse_args():
     ap.add_argument("--cap-mode", type=int, default=0, help="0 uniform capacity, 1 proportional to the target pattern")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", "--no-backward", dest="no_extras", action="store_true",
-                    help="skip the measurements beside the forward path (backward kernels, regrouping, variants)")
+                    help="skip the measurements beside the forward path (backward kernels, regrouping, variants, "
+                         "the other workloads)")
     ap.add_argument("--no-trace", action="store_true",
                     help="no HIP events inside the timed region (per-kernel times then come from an extra traced pass)")
     ap.add_argument("--graph", action="store_true",
@@ -54,29 +62,39 @@ def parse_args():
     ap.add_argument("--rotate", type=int, default=1,
                     help="number of copies of (x, send, y) that the steps cycle through, so that a small workload's "
                          "rows come from HBM and not from the 256 MB last-level cache (default 1: same buffers)")
+    ap.add_argument("--path", choices=["fused", "separate"], default="fused",
+                    help="fused: tamoe_gate_dispatch + tamoe_combine (4 launches per step); separate: tamoe_gate, "
+                         "tamoe_aux_loss, tamoe_dispatch, tamoe_combine (8 launches)")
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="target CPU time of the oracle sample")
     return ap.parse_args()
 
 
 def measured_traffic(workload: str, kernel: str):
     """HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE + WRITE_SIZE), as recorded in
-    profiles/hbm_traffic.txt: lines `<workload> <kernel> <bytes>`.  None if not recorded."""
+    profiles/hbm_traffic.txt: lines `<workload> <kernel> <bytes>`, and the commit the counters were
+    read at (its `# commit:` line).  (None, commit) if not recorded."""
+    value, commit = None, None
     try:
         with open(TRAFFIC_FILE) as f:
             for line in f:
                 parts = line.split()
+                if line.startswith("# commit:") and len(parts) >= 3:
+                    commit = parts[2]
                 if len(parts) >= 3 and not line.startswith("#") and parts[0] == workload and parts[1] == kernel:
-                    return float(parts[2])
+                    value = float(parts[2])
     except OSError:
         pass
-    return None
+    return value, commit
 
 
 def cpu_baseline(wl, W, seconds: float):
     """The oracle, as it stands, on a bounded sample of the same workload."""
     import oracle
 
-    threads = int(os.environ.get("OMP_NUM_THREADS", "0")) or min(16, os.cpu_count() or 1)
+    # every host core this process may use: the machine's share set through OMP_NUM_THREADS where the
+    # operator sets one (GPU machines hand a one-GPU job 16 cores), else all cores that are visible
+    visible = len(os.sched_getaffinity(0)) if hasattr(os, "sched_getaffinity") else (os.cpu_count() or 1)
+    threads = int(os.environ.get("OMP_NUM_THREADS", "0")) or visible
     threads = max(1, min(threads, oracle.max_threads()))
     oracle.set_threads(threads)
     beta, level = W.topology(wl)
@@ -109,7 +127,8 @@ def cpu_baseline(wl, W, seconds: float):
     S = int(min(wl.S, max(probe_S, seconds / max(t_probe, 1e-6) * probe_S)))
     S = max(64, S // 64 * 64) if wl.S >= 64 else wl.S
     t, steps = run(S)
-    out = {"value": S / t, "unit": "tokens/s", "cores": threads, "kind": "oracle",
+    out = {"value": S / t, "unit": "tokens/s", "cores": threads, "host_cores_visible": visible,
+           "cores_limited_by": "OMP_NUM_THREADS" if os.environ.get("OMP_NUM_THREADS") else "none", "kind": "oracle",
            "sample": f"first-draw sample of {S} of {wl.S} tokens of workload {wl.name}, whole path "
                      f"(setup, scores, softmax, top-k, counts, losses, slots, scatter, combine), {t:.2f} s",
            "per_step_seconds": steps}
@@ -134,15 +153,28 @@ def _median_us(T, n_rec: int) -> float:
 
 
 def _rate(nbytes: float, us: float) -> dict:
+    """Algorithmic bytes over time.  Not a measured HBM rate: bytes that a cache serves count too."""
     gbs = nbytes / (us * 1e-6) / 1e9
-    return {"algo_bytes": int(nbytes), "achieved_GBs": round(gbs, 1), "frac_of_hbm_peak": round(gbs / HBM_PEAK_GBS, 4)}
+    return {"algo_bytes": int(nbytes), "algo_GBs": round(gbs, 1), "algo_frac_of_peak": round(gbs / HBM_PEAK_GBS, 4)}
+
+
+def _timed_us(torch, fn, reps: int = 5) -> float:
+    """Median duration of fn() in microseconds, from events on the current stream (the stream fn enqueues on)."""
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(reps)]
+    for a, b in ev:
+        a.record()
+        fn()
+        b.record()
+    torch.cuda.synchronize()
+    return float(np.median([a.elapsed_time(b) for a, b in ev])) * 1e3
 
 
 class Path:
     """The buffers of one workload on the device and one step of the path over them."""
 
-    def __init__(self, T, W, torch, wl, cap_mode: int, rotate: int):
+    def __init__(self, T, W, torch, wl, cap_mode: int, rotate: int, fused: bool = True):
         self.T, self.W, self.torch, self.wl = T, W, torch, wl
+        self.fused = fused
         self.dev = dev = torch.device("cuda:0")
         torch.cuda.set_device(dev)
         inp = W.make_inputs(wl)
@@ -186,6 +218,12 @@ class Path:
         xs, sends, ys = self.sets[self.turn % self.rotate]
         self.turn += 1
         # stream=None: the binding passes torch's current stream (the capture stream under --graph)
+        if self.fused:
+            T.tamoe_gate_dispatch(xs, self.w, wl.P, wl.k, self.pen, self.cap, None, self.topk_idx, self.topk_w, self.m,
+                                  self.c_expert, self.c_device, self.loss, sends, self.slot, self.kept, self.off,
+                                  self.scd, self.ws, None)
+            T.tamoe_combine(sends, wl.S * wl.k, self.slot, self.topk_w, ys, None)
+            return
         T.tamoe_gate(xs, self.w, wl.P, wl.k, None, self.topk_idx, self.topk_w, self.m, self.c_expert, self.c_device,
                      self.ws, None)
         T.tamoe_aux_loss(self.m, self.c_expert, self.pen, wl.P, wl.S, self.loss, None)
@@ -213,14 +251,15 @@ class Path:
 
 
 def measure_probes(p: Path):
-    """Yardsticks outside the timed region: a plain copy of x into y, and (k = 2, rows a multiple of
-    1 KiB) the scatter's and the combine's bare memory operations on the realised slot table."""
-    T, wl = p.T, p.wl
+    """Yardsticks outside the timed region (kernels of libtamoe_bench.so, not of the product library):
+    a plain copy of x into y, and (k = 2, rows a multiple of 1 KiB) the scatter's and the combine's bare
+    memory operations on the realised slot table."""
+    from paper_2302_09915_amd import bench_aids as B
+
+    wl, torch = p.wl, p.torch
     S, k, row = wl.S, wl.k, p.row_bytes
-    T.tamoe_trace_start(16)
-    for _ in range(5):
-        T.tamoe_copy_probe(p.x, p.y, p.torch.cuda.current_stream())
-    copy_us = _median_us(T, T.tamoe_trace_stop())
+    B.copy_probe(p.x, p.y)
+    copy_us = _timed_us(torch, lambda: B.copy_probe(p.x, p.y))
     copy_gbs = 2.0 * S * row / (copy_us * 1e-6) / 1e9
     copy = {"bytes_moved": int(2 * S * row), "median_us": round(copy_us, 2), "GBs": round(copy_gbs, 1),
             "frac_of_hbm_peak": round(copy_gbs / HBM_PEAK_GBS, 4)}
@@ -228,19 +267,65 @@ def measure_probes(p: Path):
     if k == 2 and row % 1024 == 0:
         r0 = p.slot[:, 0].contiguous()
         r1 = p.slot[:, 1].contiguous()
-        T.tamoe_trace_start(16)
-        for _ in range(5):
-            T.tamoe_mix_probe(p.x, p.send, r0, r1, 1, None)
-        sc_us = _median_us(T, T.tamoe_trace_stop())
-        T.tamoe_trace_start(16)
-        for _ in range(5):
-            T.tamoe_mix_probe(p.send, p.y, r0, r1, 2, None)
-        ga_us = _median_us(T, T.tamoe_trace_stop())
+        B.mix_probe(p.x, p.send, r0, r1, 1)
+        sc_us = _timed_us(torch, lambda: B.mix_probe(p.x, p.send, r0, r1, 1))
+        ga_us = _timed_us(torch, lambda: B.mix_probe(p.send, p.y, r0, r1, 2))
         K0 = int((p.slot >= 0).sum().item())
         mix = {"scatter_1r2w": {"median_us": round(sc_us, 2),
                                 "GBs": round((p.live_tokens() + K0) * row / (sc_us * 1e-6) / 1e9, 1)},
                "gather_2r1w": {"median_us": round(ga_us, 2), "GBs": round((K0 + S) * row / (ga_us * 1e-6) / 1e9, 1)}}
     return copy, mix
+
+
+def measure_scatter_from_hbm(p: Path, nbytes: int):
+    """The scatter with every row of x coming from HBM: tamoe_dispatch on its own, back to back (its
+    loads and stores are streaming ones, so nothing of x stays in the last-level cache between calls).
+    In the step the scatter runs behind the gate, which leaves part of x in that cache."""
+    T, wl = p.T, p.wl
+    for _ in range(2):
+        T.tamoe_dispatch(p.x, p.topk_idx, p.cap, wl.N, wl.P, p.send, p.slot, p.kept, p.off, p.scd, p.ws, None)
+    p.sync()
+    T.tamoe_trace_filter("dispatch_copy_kernel")
+    T.tamoe_trace_start(10)
+    for _ in range(10):
+        T.tamoe_dispatch(p.x, p.topk_idx, p.cap, wl.N, wl.P, p.send, p.slot, p.kept, p.off, p.scd, p.ws, None)
+    p.sync()
+    rec = p.collect()
+    T.tamoe_trace_filter(None)
+    T.tamoe_trace_clear()
+    us = _mean_us(rec["dispatch_copy_kernel"])
+    return {"kernel": "dispatch_copy_kernel", "avg_us": round(us, 2), **_rate(nbytes, us)}
+
+
+def measure_workload(T, W, torch, name: str, steps: int, blocks: int = 3):
+    """ms per step of another configuration: eager and replayed from a HIP graph (median block)."""
+    wl = W.workload(name)
+    p = Path(T, W, torch, wl, 0, 1, fused=True)
+    out = {"S": wl.S, "d": wl.d, "N": wl.N, "k": wl.k}
+    for _ in range(5):
+        p.step()
+    p.sync()
+
+    def median_ms(run):
+        ts = []
+        for _ in range(blocks):
+            p.sync()
+            t0 = time.perf_counter()
+            for _ in range(steps):
+                run()
+            p.sync()
+            ts.append((time.perf_counter() - t0) * 1e3 / steps)
+        return round(float(np.median(ts)), 4)
+
+    out["eager_ms_per_step"] = median_ms(p.step)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        p.step()
+    for _ in range(2):
+        graph.replay()
+    out["graph_ms_per_step"] = median_ms(graph.replay)
+    out["tokens_per_s_graph"] = round(wl.S / (out["graph_ms_per_step"] * 1e-3), 1)
+    return out
 
 
 def measure_other_mode(p: Path, cap_mode: int, steps: int):
@@ -405,7 +490,7 @@ def main():
         import dataclasses
 
         wl = dataclasses.replace(wl, dtype={"f32": W.F32, "bf16": W.BF16, "f16": W.F16}[args.dtype])
-    p = Path(T, W, torch, wl, args.cap_mode, max(1, args.rotate))
+    p = Path(T, W, torch, wl, args.cap_mode, max(1, args.rotate), fused=args.path == "fused")
     S, N, k, row = wl.S, wl.N, wl.k, p.row_bytes
 
     for _ in range(max(args.warmup, 0)):
@@ -416,7 +501,7 @@ def main():
     # Pass 1 (not timed): every launch bracketed by HIP events -> the per-kernel table and the name
     # of the longest-running kernel.  Two event records per launch cost ~3 us of GPU time each, so
     # this pass is kept out of `value`.
-    launches_per_step = 9
+    launches_per_step = 10
     table_steps = max(1, min(args.steps, 20))
     T.tamoe_trace_filter(None)
     T.tamoe_trace_start(launches_per_step * table_steps)
@@ -437,18 +522,23 @@ def main():
             run_step()
         p.sync()
 
-    # Pass 2, the timed region: K steps; only the dominant kernel is bracketed by events (two
-    # records per step), which is what `roofline.achieved` is computed from.
+    # Pass 2, the timed region: `blocks` blocks of K steps, each between two synchronisations; only the
+    # dominant kernel is bracketed by events (two records per step), which is what `roofline.achieved`
+    # is computed from.  The median block gives `value`.
     traced_in_timed_region = not (args.no_trace or args.graph)
+    n_blocks = max(1, args.blocks)
     if traced_in_timed_region:
         T.tamoe_trace_filter(dominant)
-        T.tamoe_trace_start(args.steps)
-    p.sync()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        run_step()
-    p.sync()
-    elapsed = time.perf_counter() - t0
+        T.tamoe_trace_start(args.steps * n_blocks)
+    block_s = []
+    for _ in range(n_blocks):
+        p.sync()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            run_step()
+        p.sync()
+        block_s.append(time.perf_counter() - t0)
+    elapsed = float(np.median(block_s))
     dominant_live = p.collect().get(dominant) if traced_in_timed_region else None
     T.tamoe_trace_filter(None)
     T.tamoe_trace_clear()
@@ -471,6 +561,8 @@ def main():
         "gate_f32_kernel": S * row + N * row + S * k * 8,
         "select_kernel": S * N * 4 + S * k * 8,
         "dispatch_copy_kernel": live_tokens * row + K * row + S * k * 8,
+        "route_copy_kernel": live_tokens * row + K * row + S * k * 12,
+        "route_slot_kernel": S * k * 12,
         "combine_kernel": K * row + S * row + S * k * 8,
     }
     kernels = []
@@ -485,15 +577,30 @@ def main():
         live = dominant_live if dominant_live else per_kernel[dominant]
         dom_us = _mean_us(live)
         gbs = algo_bytes[dominant] / (dom_us * 1e-6) / 1e9
+        traffic, traffic_commit = measured_traffic(wl.name, dominant)
         roofline = {"kernel": dominant, "bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS,
                     "unit": "GB/s", "frac": round(gbs / HBM_PEAK_GBS, 4),
-                    "traffic": measured_traffic(wl.name, dominant),
+                    "traffic": traffic,
+                    "traffic_from": f"profiles/hbm_traffic.txt (rocprofv3 --pmc, counters read at commit {traffic_commit})",
                     "algo_bytes_per_launch": int(algo_bytes[dominant]), "avg_launch_us": round(dom_us, 2),
                     "launches_timed": len(live),
                     "timed_in": "timed region" if dominant_live else "table pass"}
 
+    # the scatter twice: as it runs in the step (behind the gate) and with x from HBM alone
+    scatter = None
+    scatter_name = next((n for n in ("route_copy_kernel", "dispatch_copy_kernel") if n in per_kernel), None)
+    if scatter_name is not None and not args.graph:
+        us = _mean_us(per_kernel[scatter_name])
+        scatter = {"behind_gate": {"kernel": scatter_name, "avg_us": round(us, 2), **_rate(algo_bytes[scatter_name], us),
+                                   "note": "part of x is served by the 256 MB last-level cache that the gate left it in"},
+                   "from_hbm": measure_scatter_from_hbm(p, algo_bytes["dispatch_copy_kernel"])}
+    others = None
+    if extras and not args.graph:
+        others = {n: measure_workload(T, W, torch, n, 50) for n in ("gpt_moe", "skewed", "small", "tiny") if n != wl.name}
+
     total_algo = algo_bytes["gate_bf16_kernel"] \
         + algo_bytes["dispatch_copy_kernel"] + algo_bytes["combine_kernel"]
+
     result = {
         "metric": "routed tokens/sec (gate+aux_loss+dispatch+combine), 1 GPU",
         "value": round(tokens_per_s, 1),
@@ -502,6 +609,9 @@ def main():
         "steps": args.steps,
         "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4),
+        "blocks": n_blocks,
+        "ms_per_step_min": round(min(block_s) * 1e3 / args.steps, 4),
+        "ms_per_step_max": round(max(block_s) * 1e3 / args.steps, 4),
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
@@ -518,12 +628,17 @@ def main():
         "copy_probe": copy_probe,
         "mix_probe": mix_probe,
         "kernels": kernels,
+        "kernels_note": "algo_GBs = algorithmic bytes / kernel time (bytes that a cache serves count too); "
+                        "avg_us from the untimed pass with events around every launch",
+        "scatter": scatter,
+        "other_workloads": others,
         "backward_kernels": backward,
         "regroup_kernel": regroup,
         "variants": variants,
         "other_capacity_mode": other_mode,
         "l_topo": float(p.loss.item()),
         "mode": "graph replay" if args.graph else "eager",
+        "path": args.path,
         "kernels_table_from": f"untimed pass of {table_steps} steps with HIP events around every launch",
     }
     if not args.no_cpu_baseline:

@@ -12,6 +12,7 @@
  *   tamoe_gate          scores x W^T, softmax, top-k, load statistics
  *   tamoe_aux_loss      topology-aware auxiliary loss l_topo (or the plain l_aux)
  *   tamoe_dispatch      capacity-limited slot assignment + scatter into the send buffer
+ *   tamoe_gate_dispatch the three calls above in one (three launches instead of seven)
  *   tamoe_combine       weighted gather of the returned rows into y
  * and around them
  *   tamoe_gate_bwd, tamoe_combine_bwd, tamoe_dispatch_bwd   backward of the path
@@ -19,7 +20,7 @@
  *   tamoe_penalty, tamoe_renorm_topk(_bwd), tamoe_dispatch_padded   variants: Norm of the penalty,
  *                       renormalised weights, fixed-size zero-padded send layout
  *   tamoe_tree_levels, tamoe_ring_table, tamoe_minmax_pattern   host: topology front-end
- *   tamoe_trace_*, tamoe_copy_probe, tamoe_mix_probe   measurement aids, not steps of the path
+ *   tamoe_trace_*       kernel timing aid (HIP events around the launches), not a step of the path
  *
  * The global exchange, the experts and the return exchange sit between tamoe_dispatch and
  * tamoe_combine and are not part of this library.
@@ -27,8 +28,10 @@
  * Conventions
  *  - Every matrix is row-major and dense.  Counts, indices and slots are int32_t.
  *  - "device" pointers are HIP device memory of the current device; "host" pointers are
- *    ordinary host memory.  The caller owns every buffer; the library allocates nothing and
- *    keeps no state between calls.  Scratch comes from the caller's workspace `ws` (device
+ *    ordinary host memory.  The caller owns every buffer; the path's functions allocate nothing and
+ *    keep no state between calls (two exceptions, both stated where they are declared: the built-in
+ *    scratch of tamoe_dispatch_static and the process-wide kernel trace, which is off unless
+ *    started).  Scratch comes from the caller's workspace `ws` (device
  *    memory, 256-byte aligned, at least tamoe_workspace_bytes() bytes).  Its content is
  *    garbage on entry and on exit; two calls that share a workspace must be ordered on one
  *    stream.
@@ -227,6 +230,30 @@ int tamoe_dispatch(const void* x, const int32_t* topk_idx, const int32_t* cap, i
                    void* ws, size_t ws_bytes, void* stream);
 
 /*
+ * The forward path up to the send buffer in one call and three kernel launches: tamoe_gate,
+ * tamoe_aux_loss and tamoe_dispatch fused (Section 3.1: gate, softmax, top-k, load statistics, local
+ * capacity; Section 4.1: per-device delivery; Section 4.3: l_topo, variable chunk sizes).  Layers of the
+ * paper's own size (hidden size 1024, a few thousand tokens per device) are bound by the number of
+ * launches, not by bytes; the gate kernel hands the slot assignment what it needs (pairs per gate
+ * workgroup, expert and choice; every pair's position inside its workgroup), so that no kernel has
+ * to read the routing again.
+ * Every output is defined as in the three separate calls, with the gate's own topk_idx as the routing:
+ *   logits (may be NULL), topk_idx, topk_w, m, c_expert, c_device     as tamoe_gate
+ *   loss (may be NULL)      l_topo with `penalty`, l_aux with penalty == NULL   as tamoe_aux_loss (0 if S == 0)
+ *   send, slot, kept_expert, expert_offset, send_count_dev            as tamoe_dispatch with `cap`
+ * Integer outputs and the send buffer are bit-identical to the separate calls'; topk_w is bit-identical;
+ * m and loss may differ from theirs in the last bits (another fixed summation order).
+ * penalty [N] float or NULL, cap [N] int32: device.  ws: tamoe_workspace_bytes(S, d, N, P, k, dtype).
+ */
+int tamoe_gate_dispatch(const void* x, const void* w, int dtype, int64_t S, int d, int N, int P, int k,
+                        const float* penalty, const int32_t* cap,
+                        float* logits, int32_t* topk_idx, float* topk_w, float* m,
+                        int32_t* c_expert, int32_t* c_device, float* loss,
+                        void* send, int32_t* slot, int32_t* kept_expert, int32_t* expert_offset,
+                        int32_t* send_count_dev,
+                        void* ws, size_t ws_bytes, void* stream);
+
+/*
  * tamoe_dispatch for callers that cannot allocate device memory or carry a workspace (code under HIP
  * graph capture, tight serving loops, harnesses that forbid hipMalloc): same arguments, outputs and
  * kernels as tamoe_dispatch without `ws`.  The pair counters live in an array inside the library's
@@ -349,35 +376,15 @@ int tamoe_regroup(const void* in, const int32_t* recv_count, int P, int E, int d
  * events.  tamoe_trace_filter restricts the bracketing to launches of the kernel with the given
  * name (NULL: every kernel again), so that a benchmark can time one kernel with two event records
  * per step instead of two per launch; it may be called at any time.
- * One trace at a time, process-wide; not thread-safe.  All pointers host.
+ * One trace at a time, process-wide: the records are shared by every thread that launches while it
+ * runs (a lock serialises their bookkeeping; records of concurrent threads interleave).  Start, stop,
+ * get and clear belong to one controlling thread.  All pointers host.
  */
 int tamoe_trace_start(int max_launches);
 int tamoe_trace_filter(const char* kernel_name);
 int tamoe_trace_stop(void);
 int tamoe_trace_get(int i, char* name, size_t name_len, float* ms);
 int tamoe_trace_clear(void);
-
-/*
- * Bandwidth yardstick for benchmarks (not a step of the path): a plain copy of `bytes` bytes
- * (a multiple of 16) from src to dst, both device, 16-byte aligned, not overlapping, with one
- * 16-byte load and store per lane.  It moves exactly 2*bytes through HBM, so its duration gives
- * the bandwidth a simple streaming kernel reaches on the machine, and hardware byte counters
- * read for it calibrate the same counters read for the kernels of the path.
- */
-int tamoe_copy_probe(const void* src, void* dst, size_t bytes, void* stream);
-
-/*
- * Row-mix yardsticks for benchmarks (not steps of the path): the bare memory operations of the
- * scatter and of the combine on caller-given row tables, with none of the method's logic.
- *   mode 1: b[row0[t]][:] = b[row1[t]][:] = a[t][:]      for t < rows   (one read, two writes)
- *   mode 2: b[t][:] = a[row0[t]][:] xor a[row1[t]][:]    for t < rows   (two reads, one write)
- * Rows are row_bytes long (a positive multiple of 1024).  `other_rows` is the number of rows of
- * the matrix that row0/row1 index (b in mode 1, a in mode 2); entries outside [0, other_rows)
- * are skipped.  In mode 1 every row number may occur at most once over both tables.  a, b, row0
- * [rows], row1 [rows]: device; a and b 16-byte aligned and not overlapping.
- */
-int tamoe_mix_probe(const void* a, void* b, const int32_t* row0, const int32_t* row1, int64_t rows,
-                    int64_t other_rows, int row_bytes, int mode, void* stream);
 
 #ifdef __cplusplus
 }

@@ -38,8 +38,8 @@ EXPORTS = (
     "tamoe_gate_bwd", "tamoe_combine_bwd", "tamoe_dispatch_bwd", "tamoe_regroup",
     "tamoe_tree_levels", "tamoe_ring_table", "tamoe_minmax_pattern",
     "tamoe_penalty", "tamoe_renorm_topk", "tamoe_renorm_topk_bwd", "tamoe_dispatch_padded",
-    "tamoe_dispatch_static",
-    "tamoe_trace_start", "tamoe_trace_filter", "tamoe_trace_stop", "tamoe_trace_get", "tamoe_trace_clear", "tamoe_copy_probe", "tamoe_mix_probe",
+    "tamoe_dispatch_static", "tamoe_gate_dispatch",
+    "tamoe_trace_start", "tamoe_trace_filter", "tamoe_trace_stop", "tamoe_trace_get", "tamoe_trace_clear",
 )
 
 
@@ -79,6 +79,9 @@ def lib() -> ctypes.CDLL:
     L.tamoe_aux_loss.argtypes = [vp, vp, vp, i32, i32, i64, vp, vp]
     L.tamoe_dispatch.restype = i32
     L.tamoe_dispatch.argtypes = [vp, vp, vp, i32, i64, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, sz, vp]
+    L.tamoe_gate_dispatch.restype = i32
+    L.tamoe_gate_dispatch.argtypes = [vp, vp, i32, i64, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp,
+                                      vp, vp, vp, vp, vp, vp, sz, vp]
     L.tamoe_dispatch_static.restype = i32
     L.tamoe_dispatch_static.argtypes = [vp, vp, vp, i32, i64, i32, i32, i32, i32, vp, vp, vp, vp, vp, vp]
     L.tamoe_combine.restype = i32
@@ -115,10 +118,6 @@ def lib() -> ctypes.CDLL:
     L.tamoe_trace_get.argtypes = [i32, ctypes.c_char_p, sz, ctypes.POINTER(ctypes.c_float)]
     L.tamoe_trace_clear.restype = i32
     L.tamoe_trace_clear.argtypes = []
-    L.tamoe_copy_probe.restype = i32
-    L.tamoe_copy_probe.argtypes = [vp, vp, sz, vp]
-    L.tamoe_mix_probe.restype = i32
-    L.tamoe_mix_probe.argtypes = [vp, vp, vp, vp, i64, i64, i32, i32, vp]
     _lib = L
     return L
 
@@ -301,6 +300,27 @@ def tamoe_dispatch(x, topk_idx, cap, N: int, P: int, send, slot, kept_expert, ex
         _dev(send_count_dev, torch.int32, "send_count_dev"), wsp, wsn, _stream(stream)))
 
 
+def tamoe_gate_dispatch(x, w, P: int, k: int, penalty, cap, logits, topk_idx, topk_w, m, c_expert, c_device, loss,
+                        send, slot, kept_expert, expert_offset, send_count_dev, ws, stream=None) -> None:
+    """Gate, loss and dispatch in one call (three launches)."""
+    S, d = x.shape
+    N = w.shape[0]
+    if w.shape[1] != d or w.dtype != x.dtype:
+        raise TamoeError(INVALID_ARG, "w must be [N,d] with the dtype of x")
+    if send is not None and (send.dtype != x.dtype or send.numel() < S * k * d):
+        raise TamoeError(INVALID_ARG, "send must have the dtype of x and room for k*S rows")
+    wsp, wsn = _ws(ws)
+    _check(lib().tamoe_gate_dispatch(
+        _dev(x, None, "x"), _dev(w, None, "w"), _dtype_code(x), S, d, N, P, k,
+        _dev(penalty, torch.float32, "penalty"), _dev(cap, torch.int32, "cap"),
+        _dev(logits, torch.float32, "logits"), _dev(topk_idx, torch.int32, "topk_idx"),
+        _dev(topk_w, torch.float32, "topk_w"), _dev(m, torch.float32, "m"),
+        _dev(c_expert, torch.int32, "c_expert"), _dev(c_device, torch.int32, "c_device"),
+        _dev(loss, torch.float32, "loss"), _dev(send, None, "send"), _dev(slot, torch.int32, "slot"),
+        _dev(kept_expert, torch.int32, "kept_expert"), _dev(expert_offset, torch.int32, "expert_offset"),
+        _dev(send_count_dev, torch.int32, "send_count_dev"), wsp, wsn, _stream(stream)))
+
+
 def tamoe_dispatch_static(x, topk_idx, cap, N: int, P: int, send, slot, kept_expert, expert_offset, send_count_dev,
                           stream=None) -> None:
     """tamoe_dispatch with the library's built-in scratch instead of a workspace (allocates nothing)."""
@@ -427,30 +447,6 @@ def tamoe_trace_clear() -> None:
     _check(lib().tamoe_trace_clear())
 
 
-def tamoe_copy_probe(src, dst, stream=None) -> None:
-    nbytes = src.numel() * src.element_size()
-    if dst.numel() * dst.element_size() < nbytes:
-        raise TamoeError(INVALID_ARG, "dst is smaller than src")
-    _check(lib().tamoe_copy_probe(_dev(src, None, "src"), _dev(dst, None, "dst"), nbytes, _stream(stream)))
-
-
-def tamoe_mix_probe(a, b, row0, row1, mode: int, stream=None) -> None:
-    """mode 1: b[row0[t]] = b[row1[t]] = a[t]; mode 2: b[t] = a[row0[t]] ^ a[row1[t]].  a, b: [rows, d] matrices."""
-    rows = row0.shape[0]
-    if mode == 1:
-        row_bytes, other = a.shape[1] * a.element_size(), b.shape[0]
-        if a.shape[0] < rows:
-            raise TamoeError(INVALID_ARG, "a has fewer rows than the row tables")
-    else:
-        row_bytes, other = b.shape[1] * b.element_size(), a.shape[0]
-        if b.shape[0] < rows:
-            raise TamoeError(INVALID_ARG, "b has fewer rows than the row tables")
-    if a.shape[1] * a.element_size() != b.shape[1] * b.element_size():
-        raise TamoeError(INVALID_ARG, "a and b must have rows of the same length")
-    _check(lib().tamoe_mix_probe(_dev(a, None, "a"), _dev(b, None, "b"), _dev(row0, torch.int32, "row0"),
-                                 _dev(row1, torch.int32, "row1"), rows, other, row_bytes, mode, _stream(stream)))
-
-
 # ---- allocating helpers -------------------------------------------------------------------
 
 def workspace(S: int, d: int, N: int, P: int, k: int, dtype: int, device="cuda") -> torch.Tensor:
@@ -509,6 +505,29 @@ def dispatch(x, topk_idx, cap, N: int, P: int, ws=None, stream=None) -> Dict[str
         ws = workspace(S, d, N, P, k, _dtype_code(x), dev)
     tamoe_dispatch(x, topk_idx, cap, N, P, out["send"], out["slot"], out["kept_expert"], out["expert_offset"],
                    out["send_count_dev"], ws, stream)
+    return out
+
+
+def gate_dispatch(x, w, P: int, k: int, penalty, cap, want_logits: bool = True, ws=None,
+                  stream=None) -> Dict[str, torch.Tensor]:
+    S, d = x.shape
+    N = w.shape[0]
+    dev = x.device
+    out = _select_outputs(S, N, P, k, dev)
+    out["logits"] = torch.empty((S, N), dtype=torch.float32, device=dev) if want_logits else None
+    out.update({
+        "loss": torch.empty((1,), dtype=torch.float32, device=dev),
+        "send": torch.empty((S * k, d), dtype=x.dtype, device=dev),
+        "slot": torch.empty((S, k), dtype=torch.int32, device=dev),
+        "kept_expert": torch.empty((N,), dtype=torch.int32, device=dev),
+        "expert_offset": torch.empty((N + 1,), dtype=torch.int32, device=dev),
+        "send_count_dev": torch.empty((P,), dtype=torch.int32, device=dev),
+    })
+    if ws is None:
+        ws = workspace(S, d, N, P, k, _dtype_code(x), dev)
+    tamoe_gate_dispatch(x, w, P, k, penalty, cap, out["logits"], out["topk_idx"], out["topk_w"], out["m"],
+                        out["c_expert"], out["c_device"], out["loss"], out["send"], out["slot"], out["kept_expert"],
+                        out["expert_offset"], out["send_count_dev"], ws, stream)
     return out
 
 

@@ -11,6 +11,9 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libtamoe.so")
+# yardstick kernels that only bench.py calls: a library of their own, nothing shared with libtamoe.so
+BENCH_CSRC = os.path.join(HERE, "csrc_bench")
+BENCH_LIB = os.path.join(HERE, "libtamoe_bench.so")
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
@@ -25,8 +28,13 @@ def sources():
     return sorted(glob.glob(os.path.join(CSRC, "*.hip")) + glob.glob(os.path.join(CSRC, "*.cpp")))
 
 
+def bench_sources():
+    return sorted(glob.glob(os.path.join(BENCH_CSRC, "*.hip")))
+
+
 def _headers():
-    return glob.glob(os.path.join(CSRC, "*.h")) + glob.glob(os.path.join(ROOT, "include", "*.h"))
+    return (glob.glob(os.path.join(CSRC, "*.h")) + glob.glob(os.path.join(ROOT, "include", "*.h"))
+            + glob.glob(os.path.join(BENCH_CSRC, "*.h")))
 
 
 def _fresh(obj: str, src: str) -> bool:
@@ -42,7 +50,8 @@ def _compile(hipcc: str, src: str, verbose: bool, incremental: bool = False):
     if incremental and _fresh(obj, src):
         return obj, subprocess.CompletedProcess([], 0, "", "")
     # .cpp files hold host code only but share the HIP headers
-    cmd = [hipcc, *HIPCC_FLAGS, "-I", os.path.join(ROOT, "include"), "-I", CSRC, "-x", "hip", "-c", src, "-o", obj]
+    inc = ["-I", BENCH_CSRC] if os.path.dirname(src) == BENCH_CSRC else ["-I", os.path.join(ROOT, "include"), "-I", CSRC]
+    cmd = [hipcc, *HIPCC_FLAGS, *inc, "-x", "hip", "-c", src, "-o", obj]
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, capture_output=True, text=True)
@@ -57,25 +66,26 @@ def build(verbose: bool = False, jobs: int = 0, incremental: bool = False) -> st
 
     hipcc = shutil.which("hipcc") or "/opt/rocm/bin/hipcc"
     os.makedirs(OBJ_DIR, exist_ok=True)
-    srcs = sources()
+    srcs = sources() + bench_sources()
     jobs = jobs or max(1, min(len(srcs), os.cpu_count() or 1, 8))
     with ThreadPoolExecutor(max_workers=jobs) as pool:
         done = list(pool.map(lambda src: _compile(hipcc, src, verbose, incremental), srcs))
-    objs = []
-    for obj, res in done:
+    objs, bench_objs = [], []
+    for src, (obj, res) in zip(srcs, done):
         if res.returncode != 0:
             sys.stderr.write(res.stdout + res.stderr)
-            raise RuntimeError("hipcc failed building libtamoe.so")
+            raise RuntimeError(f"hipcc failed compiling {src}")
         if verbose and res.stderr.strip():
             sys.stderr.write(res.stderr)
-        objs.append(obj)
-    link = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", LIB]
-    if verbose:
-        print(" ".join(link), flush=True)
-    res = subprocess.run(link, capture_output=True, text=True)
-    if res.returncode != 0:
-        sys.stderr.write(res.stdout + res.stderr)
-        raise RuntimeError("hipcc failed linking libtamoe.so")
+        (bench_objs if os.path.dirname(src) == BENCH_CSRC else objs).append(obj)
+    for out, parts in ((LIB, objs), (BENCH_LIB, bench_objs)):
+        link = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", *parts, "-o", out]
+        if verbose:
+            print(" ".join(link), flush=True)
+        res = subprocess.run(link, capture_output=True, text=True)
+        if res.returncode != 0:
+            sys.stderr.write(res.stdout + res.stderr)
+            raise RuntimeError(f"hipcc failed linking {out}")
     return LIB
 
 

@@ -249,6 +249,16 @@ static void launch_copy(const void* x, const int32_t* slot, int64_t S, int k, in
         dispatch_copy_kernel<KK, U, false><<<grid, block, 0, st>>>(src, slot, total, k, cpr, shift, dst);
 }
 
+void launch_dispatch_copy(const void* x, const int32_t* slot, int64_t S, int k, int cpr, void* send, hipStream_t st) {
+    TraceScope tr("dispatch_copy_kernel", st);
+    if (k == 1)
+        launch_copy<1, 2>(x, slot, S, k, cpr, send, st);
+    else if (k == 2)
+        launch_copy<2, 1>(x, slot, S, k, cpr, send, st);
+    else
+        launch_copy<0, 1>(x, slot, S, k, cpr, send, st);
+}
+
 // Fixed-size layout: zero rows e*C + kept[e] .. (e+1)*C - 1 of every expert.  Workgroup (e, part)
 // clears a contiguous share of expert e's unused chunks: stores only, so nothing waits on memory.
 __global__ __launch_bounds__(kThreads) void dispatch_pad_fill_kernel(const int32_t* __restrict__ kept_expert, int cpr,
@@ -301,15 +311,7 @@ static int dispatch_impl(const char* fn, const void* x, const int32_t* topk_idx,
                 topk_idx, cap, tile_count, expert_offset, S, N, k, (int)n_ct, pad_C, slot);
         }
         if ((rc = check_launch(fn, "dispatch_slot_kernel")) != TAMOE_OK) return rc;
-        {
-            TraceScope tr("dispatch_copy_kernel", st);
-            if (k == 1)
-                launch_copy<1, 2>(x, slot, S, k, cpr, send, st);
-            else if (k == 2)
-                launch_copy<2, 1>(x, slot, S, k, cpr, send, st);
-            else
-                launch_copy<0, 1>(x, slot, S, k, cpr, send, st);
-        }
+        launch_dispatch_copy(x, slot, S, k, cpr, send, st);
         if ((rc = check_launch(fn, "dispatch_copy_kernel")) != TAMOE_OK) return rc;
     }
     if (pad_C > 0) {

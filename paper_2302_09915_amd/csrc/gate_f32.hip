@@ -15,11 +15,11 @@ void launch_gate_f32_split(const GateLaunch& g) {
         if (ktail)                                                                                                \
             gate_f32_split_kernel<NBV, true><<<grid, dim3(64), 0, g.st>>>(g.x, g.w, g.S, g.d_units, g.N, g.k,     \
                                                                            g.logits, g.topk_idx, g.topk_w,         \
-                                                                           g.m_part, g.c_part, (int)g.blocks);     \
+                                                                           g.stats);                               \
         else                                                                                                      \
             gate_f32_split_kernel<NBV, false><<<grid, dim3(64), 0, g.st>>>(g.x, g.w, g.S, g.d_units, g.N, g.k,    \
                                                                             g.logits, g.topk_idx, g.topk_w,        \
-                                                                            g.m_part, g.c_part, (int)g.blocks);    \
+                                                                            g.stats);                              \
     } while (0)
     if (g.N <= 32)
         TAMOE_SPLIT(1);

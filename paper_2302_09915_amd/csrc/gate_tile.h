@@ -180,15 +180,24 @@ __device__ __forceinline__ void load_logits_tile(float (&sc)[NB][16], int lane, 
     }
 }
 
+// What a lane keeps of its token's selection for the block-wide step that follows (finish_block).
+struct TokenPairs {
+    int expert[TAMOE_MAX_K];   // selected expert of choice j, -1 if none (token beyond S, no valid score)
+    int rank[TAMOE_MAX_K];     // earlier tokens of this wavefront with the same expert at choice j
+};
+
 // Selection on a 32-token tile held in the accumulator layout described above.
 // sc[nb][v]: score of expert_of(nb, v, lane>>5) for token `token` (lane & 31 within the tile).
-// m_wave: LDS, [>= NB*32] floats owned by this wavefront; hist: LDS, [>= NB*32] ints of the block.
+// m_wave: LDS, [>= NB*32] floats owned by this wavefront; pairs_wave: LDS, [>= k*NB*32] ints owned by this
+// wavefront, receives the number of its tokens that chose expert e at choice j in [j*NB*32 + e].
 template <int NB>
 __device__ __forceinline__ void select_tile(float (&sc)[NB][16], int lane, int64_t token, bool token_ok, int N,
                                             int k, float* __restrict__ logits, int32_t* __restrict__ topk_idx,
-                                            float* __restrict__ topk_w, float* m_wave, int32_t* hist,
-                                            float* tile, int64_t S) {
+                                            float* __restrict__ topk_w, float* m_wave, int32_t* pairs_wave,
+                                            float* tile, int64_t S, TokenPairs& tp) {
     const int half = lane >> 5;
+    constexpr int ROWS = NB * 32;
+    for (int q = lane; q < k * ROWS; q += 64) pairs_wave[q] = 0;
     if (logits != nullptr) store_logits_tile<NB>(sc, lane, token, N, logits, tile, S);
     if (N < NB * 32) {  // uniform
 #pragma unroll
@@ -292,8 +301,30 @@ __device__ __forceinline__ void select_tile(float (&sc)[NB][16], int lane, int64
             if (j < k) {
                 topk_idx[token * k + j] = sel_i[j];
                 topk_w[token * k + j] = __builtin_amdgcn_exp2f((sel_v[j] - mx) * 1.44269504088896340736f) / den;
-                if (sel_i[j] >= 0 && sel_i[j] < N) atomicAdd(&hist[sel_i[j]], 1);
             }
+        }
+    }
+
+    // Pairs per (choice, expert) of this wavefront, and for every pair the number of earlier tokens of
+    // the wavefront with the same expert at the same choice (tokens are in lane order): what the
+    // capacity-limited slot assignment needs from the gate.  Both halves hold the same selection.
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");   // the zeroes above before the atomics
+    const int r_tok = lane & 31;
+#pragma unroll
+    for (int j = 0; j < TAMOE_MAX_K; ++j) {
+        tp.expert[j] = -1;
+        tp.rank[j] = 0;
+        if (j < k) {
+            const int mine = (token_ok && sel_i[j] >= 0 && sel_i[j] < N) ? sel_i[j] : -1;
+            int rank = 0;
+#pragma unroll
+            for (int rr = 0; rr < 31; ++rr) {
+                const int other = __builtin_amdgcn_readlane(mine, rr);
+                rank += (rr < r_tok && other == mine) ? 1 : 0;
+            }
+            tp.expert[j] = mine;
+            tp.rank[j] = rank;
+            if (half == 0 && mine >= 0) atomicAdd(&pairs_wave[j * ROWS + mine], 1);
         }
     }
 
@@ -321,19 +352,44 @@ __device__ __forceinline__ void select_tile(float (&sc)[NB][16], int lane, int64
     }
 }
 
-// Folds the wavefronts' sums and the block histogram into the per-workgroup partial arrays
-// (expert-major, so that the finalize kernel reads them contiguously).
+// Block-wide end of the selection: per-workgroup probability sums and pair counts, and every pair's
+// position among the pairs of its workgroup (pairs of earlier wavefronts + rank inside its own).
+// pairs: LDS, wavefront w owns [w*pairs_stride, + k*NB*32).
 template <int NB, int WAVES>
-__device__ __forceinline__ void store_block_partials(const float (*m_w)[NB * 32], const int32_t* hist, int N,
-                                                     int n_blocks, float* __restrict__ m_part,
-                                                     int32_t* __restrict__ c_part) {
+__device__ __forceinline__ void finish_block(const float (*m_w)[NB * 32], const int32_t* pairs, int pairs_stride,
+                                             const TokenPairs& tp, int lane, int wave, int64_t token, bool token_ok,
+                                             int N, int k, const GateStats& gs) {
+    constexpr int ROWS = NB * 32;
+    if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) *gs.done = 0u;
     __syncthreads();
+    if ((lane >> 5) == 0 && token_ok) {
+#pragma unroll
+        for (int j = 0; j < TAMOE_MAX_K; ++j) {
+            if (j < k) {
+                int before = 0;
+                if (tp.expert[j] >= 0) {
+#pragma unroll
+                    for (int w = 0; w < WAVES; ++w)
+                        if (w < wave) before += pairs[w * pairs_stride + j * ROWS + tp.expert[j]];
+                }
+                gs.local_pos[token * k + j] = before + tp.rank[j];
+            }
+        }
+    }
     for (int e = threadIdx.x; e < N; e += WAVES * 64) {
         float s = 0.f;
 #pragma unroll
         for (int w = 0; w < WAVES; ++w) s += m_w[w][e];
-        m_part[(size_t)e * n_blocks + blockIdx.x] = s;
-        c_part[(size_t)e * n_blocks + blockIdx.x] = hist[e];
+        gs.m_part[(size_t)e * gs.n_blocks + blockIdx.x] = s;
+    }
+    for (int q = threadIdx.x; q < k * ROWS; q += WAVES * 64) {
+        const int j = q / ROWS, e = q - j * ROWS;
+        if (e < N) {
+            int32_t c = 0;
+#pragma unroll
+            for (int w = 0; w < WAVES; ++w) c += pairs[w * pairs_stride + q];
+            gs.tile_pairs[(size_t)e * gs.pitch + (size_t)j * gs.n_blocks + blockIdx.x] = c;
+        }
     }
 }
 
@@ -348,8 +404,7 @@ __device__ __forceinline__ void store_block_partials(const float (*m_w)[NB * 32]
 template <int NB, int WAVES, bool KTAIL, int ET, bool SPLIT = false>
 __device__ __forceinline__ void gate_mfma_tile(
     const uint16_t* __restrict__ x, const uint16_t* __restrict__ w, int64_t S, int d, int N, int k,
-    float* __restrict__ logits, int32_t* __restrict__ topk_idx, float* __restrict__ topk_w,
-    float* __restrict__ m_part, int32_t* __restrict__ c_part, int n_blocks) {
+    float* __restrict__ logits, int32_t* __restrict__ topk_idx, float* __restrict__ topk_w, const GateStats gs) {
     constexpr int T = WAVES * 64;
     constexpr int ROWS = NB * 32;        // expert rows of the W tile
     constexpr int TOK = WAVES * 32;      // token rows of the x tile
@@ -359,7 +414,6 @@ __device__ __forceinline__ void gate_mfma_tile(
     __shared__ __attribute__((aligned(16))) unsigned char w_lds[2][ROWS * kLdsRow];
     __shared__ __attribute__((aligned(16))) unsigned char x_lds[2][TOK * kLdsRow];
     __shared__ float m_w[WAVES][ROWS];
-    __shared__ int32_t hist[ROWS];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -370,7 +424,6 @@ __device__ __forceinline__ void gate_mfma_tile(
     const int64_t token = tile0 + wave * 32 + r;
     const bool token_ok = token < S;
 
-    for (int e = tid; e < ROWS; e += T) hist[e] = 0;
     for (int q = tid; q < WAVES * ROWS; q += T) (&m_w[0][0])[q] = 0.f;
 
     const int all_chunks = (d + kKC - 1) / kKC;
@@ -546,46 +599,53 @@ __device__ __forceinline__ void gate_mfma_tile(
     for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
         for (int v = 0; v < 16; ++v) sc[nb][v] = acc[nb][v];
-    // the K loop is over (its last stage ended with a barrier): x_lds is free, 9216 bytes per wavefront
-    float* tile = reinterpret_cast<float*>(&x_lds[0][0]) + wave * (2 * 32 * kLdsRow / 4);
-    static_assert(2 * 32 * kLdsRow >= 32 * kTileRow * 4, "logits tile must fit the wavefront's share of x_lds");
+    // the K loop is over (its last stage ended with a barrier): x_lds is free, 9216 bytes per wavefront:
+    // the logits tile first, the wavefront's pair counts (at most 8 choices x 128 experts) behind it
+    constexpr int kWaveWords = 2 * 32 * kLdsRow / 4;
+    constexpr int kTileWords = 32 * kTileRow;
+    static_assert(kWaveWords >= kTileWords + TAMOE_MAX_K * TAMOE_MAX_EXPERTS,
+                  "logits tile and pair counts must fit the wavefront's share of x_lds");
+    float* tile = reinterpret_cast<float*>(&x_lds[0][0]) + wave * kWaveWords;
     if constexpr (SPLIT) {
         store_logits_tile<NB>(sc, lane, token, N, logits + (size_t)blockIdx.y * (size_t)S * N, tile, S);
     } else {
-        select_tile<NB>(sc, lane, token, token_ok, N, k, logits, topk_idx, topk_w, m_w[wave], hist, tile, S);
-        store_block_partials<NB, WAVES>(m_w, hist, N, n_blocks, m_part, c_part);
+        int32_t* pairs = reinterpret_cast<int32_t*>(&x_lds[0][0]) + kTileWords;
+        TokenPairs tp;
+        select_tile<NB>(sc, lane, token, token_ok, N, k, logits, topk_idx, topk_w, m_w[wave],
+                        pairs + wave * kWaveWords, tile, S, tp);
+        finish_block<NB, WAVES>(m_w, pairs, kWaveWords, tp, lane, wave, token, token_ok, N, k, gs);
     }
 }
 
 #define TAMOE_GATE_ARGS                                                                                     \
     const uint16_t *__restrict__ x, const uint16_t *__restrict__ w, int64_t S, int d, int N, int k,         \
         float *__restrict__ logits, int32_t *__restrict__ topk_idx, float *__restrict__ topk_w,             \
-        float *__restrict__ m_part, int32_t *__restrict__ c_part, int n_blocks
+        const GateStats gs
 
 template <int NB, int WAVES, bool KTAIL>
 __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu((NB == 4 && WAVES < 4) ? 1 : 2)))
 void gate_bf16_kernel(TAMOE_GATE_ARGS) {
-    gate_mfma_tile<NB, WAVES, KTAIL, TAMOE_BF16>(x, w, S, d, N, k, logits, topk_idx, topk_w, m_part, c_part, n_blocks);
+    gate_mfma_tile<NB, WAVES, KTAIL, TAMOE_BF16>(x, w, S, d, N, k, logits, topk_idx, topk_w, gs);
 }
 
 template <int NB, int WAVES, bool KTAIL>
 __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu((NB == 4 && WAVES < 4) ? 1 : 2)))
 void gate_f16_kernel(TAMOE_GATE_ARGS) {
-    gate_mfma_tile<NB, WAVES, KTAIL, TAMOE_F16>(x, w, S, d, N, k, logits, topk_idx, topk_w, m_part, c_part, n_blocks);
+    gate_mfma_tile<NB, WAVES, KTAIL, TAMOE_F16>(x, w, S, d, N, k, logits, topk_idx, topk_w, gs);
 }
 
 // fp32 storage: x and w point to floats, d counts 2-byte units (twice the hidden size)
 template <int NB, int WAVES, bool KTAIL>
 __global__ __launch_bounds__(WAVES * 64) __attribute__((amdgpu_waves_per_eu((NB == 4 && WAVES < 4) ? 1 : 2)))
 void gate_f32_kernel(TAMOE_GATE_ARGS) {
-    gate_mfma_tile<NB, WAVES, KTAIL, TAMOE_F32>(x, w, S, d, N, k, logits, topk_idx, topk_w, m_part, c_part, n_blocks);
+    gate_mfma_tile<NB, WAVES, KTAIL, TAMOE_F32>(x, w, S, d, N, k, logits, topk_idx, topk_w, gs);
 }
 
 // fp32 storage, small batches: one wavefront per workgroup, K split over grid rows (see SPLIT above)
 template <int NB, bool KTAIL>
 __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(1)))
 void gate_f32_split_kernel(TAMOE_GATE_ARGS) {
-    gate_mfma_tile<NB, 1, KTAIL, TAMOE_F32, true>(x, w, S, d, N, k, logits, topk_idx, topk_w, m_part, c_part, n_blocks);
+    gate_mfma_tile<NB, 1, KTAIL, TAMOE_F32, true>(x, w, S, d, N, k, logits, topk_idx, topk_w, gs);
 }
 #undef TAMOE_GATE_ARGS
 
@@ -598,7 +658,7 @@ inline const char* gate_kernel_name(int et) {
 template <int NB, int ET>
 inline void launch_gate_mfma(int waves, int64_t blocks, hipStream_t st, const uint16_t* x, const uint16_t* w,
                              int64_t S, int d, int N, int k, float* logits, int32_t* topk_idx, float* topk_w,
-                             float* m_part, int32_t* c_part) {
+                             const GateStats& gs) {
     const dim3 grid((unsigned)blocks);
     const bool ktail = d % kKC != 0;
     TraceScope tr(gate_kernel_name(ET), st);
@@ -606,13 +666,13 @@ inline void launch_gate_mfma(int waves, int64_t blocks, hipStream_t st, const ui
     do {                                                                                                           \
         if constexpr (ET == TAMOE_F32)                                                                             \
             gate_f32_kernel<NB, WV, KT><<<grid, dim3(WV * 64), 0, st>>>(x, w, S, d, N, k, logits, topk_idx, topk_w, \
-                                                                         m_part, c_part, (int)blocks);              \
+                                                                         gs);                                       \
         else if constexpr (ET == TAMOE_F16)                                                                        \
             gate_f16_kernel<NB, WV, KT><<<grid, dim3(WV * 64), 0, st>>>(x, w, S, d, N, k, logits, topk_idx, topk_w, \
-                                                                         m_part, c_part, (int)blocks);              \
+                                                                         gs);                                       \
         else                                                                                                       \
             gate_bf16_kernel<NB, WV, KT><<<grid, dim3(WV * 64), 0, st>>>(x, w, S, d, N, k, logits, topk_idx,       \
-                                                                          topk_w, m_part, c_part, (int)blocks);     \
+                                                                          topk_w, gs);                              \
     } while (0)
     if (waves == 8) {
         if constexpr (NB >= 2) {
@@ -642,21 +702,20 @@ struct GateLaunch {
     float* logits;        // caller's logits (may be NULL); for a split launch the partial-score buffer
     int32_t* topk_idx;
     float* topk_w;
-    float* m_part;
-    int32_t* c_part;
+    GateStats stats;      // n_blocks and pitch are those of this launch
 };
 
 template <int ET>
 inline void launch_gate_typed(const GateLaunch& g) {
     if (g.N <= 32)
         launch_gate_mfma<1, ET>(g.waves, g.blocks, g.st, g.x, g.w, g.S, g.d_units, g.N, g.k, g.logits, g.topk_idx,
-                                g.topk_w, g.m_part, g.c_part);
+                                g.topk_w, g.stats);
     else if (g.N <= 64)
         launch_gate_mfma<2, ET>(g.waves, g.blocks, g.st, g.x, g.w, g.S, g.d_units, g.N, g.k, g.logits, g.topk_idx,
-                                g.topk_w, g.m_part, g.c_part);
+                                g.topk_w, g.stats);
     else
         launch_gate_mfma<4, ET>(g.waves, g.blocks, g.st, g.x, g.w, g.S, g.d_units, g.N, g.k, g.logits, g.topk_idx,
-                                g.topk_w, g.m_part, g.c_part);
+                                g.topk_w, g.stats);
 }
 
 // One definition each, in the translation unit of the element type.

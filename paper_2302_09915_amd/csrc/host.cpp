@@ -3,7 +3,9 @@
 #include <cmath>
 #include <cstdio>
 #include <cstring>
+#include <atomic>
 #include <map>
+#include <mutex>
 #include <vector>
 
 #include "internal.h"
@@ -48,8 +50,12 @@ Workspace workspace_layout(int64_t S, int N, int k, int dtype) {
     const size_t gb = (size_t)gate_blocks_max(S);
     w.m_part = off;
     off = align_up(off + gb * N * sizeof(float), 256);
-    w.c_part = off;
-    off = align_up(off + gb * N * sizeof(int32_t), 256);
+    w.tile_pairs = off;
+    off = align_up(off + (size_t)pair_pitch(k, (int64_t)gb) * N * sizeof(int32_t), 256);
+    w.local_pos = off;
+    off = align_up(off + (size_t)S * k * sizeof(int32_t), 256);
+    w.done = off;
+    off += 256;
     w.tile_count = off;
     off = align_up(off + (size_t)k * count_tiles(S) * N * sizeof(int32_t), 256);
     // last, so that the other offsets do not depend on the storage type; sized for the largest batch
@@ -101,8 +107,9 @@ int check_launch(const char* fn, const char* kernel) {
 }
 
 // ---- kernel timing aid --------------------------------------------------------------------
-bool g_trace_on = false;
+std::atomic<bool> g_trace_on{false};
 namespace {
+std::mutex g_trace_lock;              // guards everything below
 struct TraceRecord {
     const char* kernel;
     hipEvent_t begin, end;
@@ -113,18 +120,25 @@ bool g_open = false;                  // a begin without its end
 char g_filter[64] = "";               // "" = every kernel
 }  // namespace
 
-void trace_begin(const char* kernel, hipStream_t st) {
-    if (g_filter[0] != '\0' && std::strcmp(kernel, g_filter) != 0) return;
+// Opens a record for this launch and returns true, or returns false (filtered out, table full, or a
+// launch of another thread is being bracketed: records never nest).
+bool trace_begin(const char* kernel, hipStream_t st) {
+    std::lock_guard<std::mutex> hold(g_trace_lock);
+    if (g_open) return false;
+    if (g_filter[0] != '\0' && std::strcmp(kernel, g_filter) != 0) return false;
     if (g_used >= g_records.size()) {
         g_trace_on = false;
-        return;
+        return false;
     }
     g_records[g_used].kernel = kernel;
     g_open = hipEventRecord(g_records[g_used].begin, st) == hipSuccess;
+    return g_open;
 }
 
+// Closes the record that the caller's trace_begin opened.
 void trace_end(hipStream_t st) {
-    if (!g_open) return;
+    std::lock_guard<std::mutex> hold(g_trace_lock);
+    if (!g_open) return;              // cleared in between
     g_open = false;
     if (hipEventRecord(g_records[g_used].end, st) == hipSuccess) ++g_used;
     if (g_used >= g_records.size()) g_trace_on = false;
@@ -135,6 +149,7 @@ void trace_end(hipStream_t st) {
 using namespace tamoe;
 
 extern "C" int tamoe_trace_clear(void) {
+    std::lock_guard<std::mutex> hold(g_trace_lock);
     g_trace_on = false;
     for (auto& r : g_records) {
         (void)hipEventDestroy(r.begin);
@@ -151,11 +166,16 @@ extern "C" int tamoe_trace_start(int max_launches) {
     if (max_launches <= 0 || max_launches > (1 << 20))
         return fail(TAMOE_INVALID_ARG, "tamoe_trace_start: max_launches = %d outside (0, 2^20]", max_launches);
     tamoe_trace_clear();
+    std::lock_guard<std::mutex> hold(g_trace_lock);
     g_records.reserve((size_t)max_launches);
     for (int i = 0; i < max_launches; ++i) {
         TraceRecord r{nullptr, nullptr, nullptr};
         if (hipEventCreate(&r.begin) != hipSuccess || hipEventCreate(&r.end) != hipSuccess) {
-            tamoe_trace_clear();
+            for (auto& q : g_records) {
+                (void)hipEventDestroy(q.begin);
+                (void)hipEventDestroy(q.end);
+            }
+            g_records.clear();
             return fail(TAMOE_HIP_ERROR, "tamoe_trace_start: hipEventCreate failed");
         }
         g_records.push_back(r);
@@ -166,6 +186,7 @@ extern "C" int tamoe_trace_start(int max_launches) {
 
 extern "C" int tamoe_trace_filter(const char* kernel_name) {
     clear_error();
+    std::lock_guard<std::mutex> hold(g_trace_lock);
     if (kernel_name == nullptr) {
         g_filter[0] = '\0';
         return TAMOE_OK;
@@ -179,6 +200,7 @@ extern "C" int tamoe_trace_filter(const char* kernel_name) {
 extern "C" int tamoe_trace_stop(void) {
     clear_error();
     g_trace_on = false;
+    std::lock_guard<std::mutex> hold(g_trace_lock);
     if (g_used > 0 && hipEventSynchronize(g_records[g_used - 1].end) != hipSuccess)
         return -fail(TAMOE_HIP_ERROR, "tamoe_trace_stop: hipEventSynchronize failed");
     return (int)g_used;
@@ -186,6 +208,7 @@ extern "C" int tamoe_trace_stop(void) {
 
 extern "C" int tamoe_trace_get(int i, char* name, size_t name_len, float* ms) {
     clear_error();
+    std::lock_guard<std::mutex> hold(g_trace_lock);
     if (i < 0 || (size_t)i >= g_used) return fail(TAMOE_INVALID_ARG, "tamoe_trace_get: record %d does not exist", i);
     if (name != nullptr && name_len > 0) {
         std::snprintf(name, name_len, "%s", g_records[i].kernel);

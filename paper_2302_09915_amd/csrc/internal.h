@@ -3,6 +3,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <cstdarg>
 #include <cstddef>
 #include <cstdint>
@@ -42,16 +43,53 @@ constexpr int kCountTile = 1024;
 inline int64_t count_tiles(int64_t S) { return ceil_div(S, kCountTile); }
 
 // ---- workspace layout -----------------------------------------------------------------------
+// Row pitch of the gate's pair-count table for `blocks` gate workgroups: a multiple of 64 entries, so
+// that every expert's row starts on a 256-byte boundary and can be read in 16-byte pieces.
+inline int64_t pair_pitch(int k, int64_t blocks) { return (int64_t)align_up((size_t)((int64_t)k * blocks), 64); }
+
 struct Workspace {
-    size_t m_part;      // float  [N][gate_blocks_max]   per-workgroup sums of gate probabilities
-    size_t c_part;      // int32  [N][gate_blocks_max]   per-workgroup selection counts
-    size_t tile_count;  // int32  [k][count_tiles][N]    pair counts, then their exclusive prefix
-    size_t part_logits; // float  [kMaxKSplits][S][N]    partial scores of a K-split gate (small S only)
+    size_t m_part;      // float  [N][gate blocks]        per-workgroup sums of gate probabilities
+    size_t tile_pairs;  // int32  [N][pair_pitch]         gate: pairs per (expert; choice, workgroup), then their
+                        //                                exclusive prefix in priority order
+    size_t local_pos;   // int32  [S][k]                  gate: position of a pair among those of its workgroup
+    size_t done;        // uint32 [1]                     ticket counter, reset by every gate launch
+    size_t tile_count;  // int32  [k][count_tiles][N]     dispatch on given routing: pair counts, then their prefix
+    size_t part_logits; // float  [kMaxKSplits][S][N]     partial scores of a K-split gate (small S only)
     size_t total;
 };
 // dtype: only fp32 storage adds the partial-score region (the gate's K split); every other region sits
 // at the same offset for every storage type.
 Workspace workspace_layout(int64_t S, int N, int k, int dtype = TAMOE_BF16);
+
+// Where the block-wide results of the selection go (device memory, the caller's workspace).
+struct GateStats {
+    float* m_part;        // [N][n_blocks]      sums of gate probabilities per workgroup
+    int32_t* tile_pairs;  // [N][pitch]         pairs per (expert; choice j, workgroup b) at [e*pitch + j*n_blocks + b]
+    int32_t* local_pos;   // [S][k]             earlier pairs of the same workgroup with the same expert and choice
+    uint32_t* done;       // [1]                set to zero by the gate's first workgroup (a ticket counter for
+                          //                    the kernel behind it)
+    int n_blocks;
+    int pitch;
+};
+
+// What the gate stage left in the workspace for the stages behind it.
+struct GateRun {
+    GateStats stats;
+    int tile_tokens;      // tokens per gate workgroup: token t belongs to workgroup t / tile_tokens
+};
+// The gate's kernels up to the per-workgroup partial results (no finalize).  Arguments are those of
+// tamoe_gate / tamoe_select, already checked.
+int run_gate_stage(const char* fn, const void* x, const void* w, int dtype, int64_t S, int d, int N, int k,
+                   float* logits, int32_t* topk_idx, float* topk_w, void* ws, const Workspace& lay, hipStream_t st,
+                   GateRun* run);
+int run_select_stage(const char* fn, const float* logits, int64_t S, int N, int k, int32_t* topk_idx, float* topk_w,
+                     void* ws, const Workspace& lay, hipStream_t st, GateRun* run);
+int check_select_outputs(const char* fn, int64_t S, int32_t* topk_idx, float* topk_w, float* m, int32_t* c_expert,
+                         int32_t* c_device, void* ws, size_t ws_bytes, const Workspace& lay);
+
+// The scatter of tamoe_dispatch on a finished slot table: send[slot[t][j]] = x[t] for every slot >= 0.
+// cpr: 16-byte chunks per row.
+void launch_dispatch_copy(const void* x, const int32_t* slot, int64_t S, int k, int cpr, void* send, hipStream_t st);
 
 // log2(v) if v is a power of two, else -1.
 inline int pow2_shift(int v) {
@@ -85,14 +123,14 @@ int check_launch(const char* fn, const char* kernel);
 
 // Brackets one kernel launch with a pair of events while a trace is running (tamoe_trace_start);
 // a single branch otherwise.
-extern bool g_trace_on;
-void trace_begin(const char* kernel, hipStream_t st);
+extern std::atomic<bool> g_trace_on;
+bool trace_begin(const char* kernel, hipStream_t st);
 void trace_end(hipStream_t st);
 struct TraceScope {
     hipStream_t st;
     bool on;
-    TraceScope(const char* kernel, hipStream_t s) : st(s), on(g_trace_on) {
-        if (on) trace_begin(kernel, st);
+    TraceScope(const char* kernel, hipStream_t s) : st(s), on(false) {
+        if (g_trace_on.load(std::memory_order_relaxed)) on = trace_begin(kernel, st);
     }
     ~TraceScope() {
         if (on) trace_end(st);

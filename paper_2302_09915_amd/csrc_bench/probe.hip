@@ -1,9 +1,17 @@
-// tamoe_copy_probe: a plain 16-byte-per-lane device copy.  Not a step of the path: it is the
-// yardstick the benchmark uses for the HBM bandwidth a simple streaming kernel reaches on this
-// machine, and the kernel of known size against which hardware byte counters are calibrated.
-#include "internal.h"
+// Bandwidth yardsticks for the benchmark (libtamoe_bench.so; not part of the product library):
+// tamoe_copy_probe, a plain 16-byte-per-lane device copy (the HBM bandwidth a simple streaming kernel
+// reaches on this machine, and the kernel of known size against which hardware byte counters are
+// calibrated), and tamoe_mix_probe, the bare memory operations of the scatter and of the combine on
+// given row tables.  Self-contained: no code shared with the library's kernels.
+#include <hip/hip_runtime.h>
 
-namespace tamoe {
+#include <cstdint>
+
+#include "tamoe_bench.h"
+
+namespace {
+
+typedef uint32_t vec16 __attribute__((ext_vector_type(4)));
 
 constexpr int kProbeThreads = 256;
 constexpr int kProbeUnroll = 4;
@@ -52,31 +60,23 @@ __global__ __launch_bounds__(kProbeThreads) void mix_probe_kernel(const vec16* _
     }
 }
 
-}  // namespace tamoe
+}  // namespace
 
-using namespace tamoe;
+static bool aligned16(const void* p) { return p != nullptr && reinterpret_cast<uintptr_t>(p) % 16 == 0; }
 
 extern "C" int tamoe_mix_probe(const void* a, void* b, const int32_t* row0, const int32_t* row1, int64_t rows,
                                int64_t other_rows, int row_bytes, int mode, void* stream) {
-    const char* fn = "tamoe_mix_probe";
-    clear_error();
-    int rc;
-    if (mode != 1 && mode != 2) return fail(TAMOE_INVALID_ARG, "%s: mode %d is neither 1 (scatter) nor 2 (gather)", fn, mode);
-    if (rows < 0 || other_rows < 0) return fail(TAMOE_INVALID_ARG, "%s: negative row count", fn);
-    if (row_bytes <= 0 || row_bytes % 1024 != 0)
-        return fail(TAMOE_UNSUPPORTED, "%s: row_bytes = %d is not a positive multiple of 1024", fn, row_bytes);
-    if (rows == 0) return TAMOE_OK;
-    if ((rc = check_ptr(fn, "a", a, 16)) != TAMOE_OK) return rc;
-    if ((rc = check_ptr(fn, "b", b, 16)) != TAMOE_OK) return rc;
-    if ((rc = check_ptr(fn, "row0", row0, 4)) != TAMOE_OK) return rc;
-    if ((rc = check_ptr(fn, "row1", row1, 4)) != TAMOE_OK) return rc;
+    if (mode != 1 && mode != 2) return TAMOE_BENCH_BAD_ARG;
+    if (rows < 0 || other_rows < 0) return TAMOE_BENCH_BAD_ARG;
+    if (row_bytes <= 0 || row_bytes % 1024 != 0) return TAMOE_BENCH_BAD_ARG;
+    if (rows == 0) return TAMOE_BENCH_OK;
+    if (!aligned16(a) || !aligned16(b) || row0 == nullptr || row1 == nullptr) return TAMOE_BENCH_BAD_ARG;
     const int cpr = row_bytes / 16;
     const int64_t total = rows * cpr;
-    const int64_t blocks = ceil_div(total, kProbeThreads);
-    if (rows >= ((int64_t)1 << 31) || blocks > 0x7fffffff) return fail(TAMOE_UNSUPPORTED, "%s: too many rows", fn);
+    const int64_t blocks = (total + kProbeThreads - 1) / kProbeThreads;
+    if (rows >= ((int64_t)1 << 31) || blocks > 0x7fffffff) return TAMOE_BENCH_BAD_ARG;
     hipStream_t st = static_cast<hipStream_t>(stream);
     {
-        TraceScope tr(mode == 1 ? "mix_probe_scatter_kernel" : "mix_probe_gather_kernel", st);
         if (mode == 1)
             mix_probe_kernel<1><<<dim3((unsigned)blocks), dim3(kProbeThreads), 0, st>>>(
                 static_cast<const vec16*>(a), static_cast<vec16*>(b), row0, row1, total, cpr, other_rows);
@@ -84,25 +84,19 @@ extern "C" int tamoe_mix_probe(const void* a, void* b, const int32_t* row0, cons
             mix_probe_kernel<2><<<dim3((unsigned)blocks), dim3(kProbeThreads), 0, st>>>(
                 static_cast<const vec16*>(a), static_cast<vec16*>(b), row0, row1, total, cpr, other_rows);
     }
-    return check_launch(fn, "mix_probe_kernel");
+    return hipGetLastError() == hipSuccess ? TAMOE_BENCH_OK : TAMOE_BENCH_HIP_ERROR;
 }
 
 extern "C" int tamoe_copy_probe(const void* src, void* dst, size_t bytes, void* stream) {
-    const char* fn = "tamoe_copy_probe";
-    clear_error();
-    int rc;
-    if (bytes == 0) return TAMOE_OK;
-    if (bytes % 16 != 0) return fail(TAMOE_INVALID_ARG, "%s: bytes = %zu is not a multiple of 16", fn, bytes);
-    if ((rc = check_ptr(fn, "src", src, 16)) != TAMOE_OK) return rc;
-    if ((rc = check_ptr(fn, "dst", dst, 16)) != TAMOE_OK) return rc;
+    if (bytes == 0) return TAMOE_BENCH_OK;
+    if (bytes % 16 != 0 || !aligned16(src) || !aligned16(dst)) return TAMOE_BENCH_BAD_ARG;
     const size_t n_vec = bytes / 16;
     const size_t blocks = (n_vec + kProbeThreads * kProbeUnroll - 1) / (kProbeThreads * kProbeUnroll);
-    if (blocks > 0x7fffffffu) return fail(TAMOE_UNSUPPORTED, "%s: more than 2^31 blocks", fn);
+    if (blocks > 0x7fffffffu) return TAMOE_BENCH_BAD_ARG;
     hipStream_t st = static_cast<hipStream_t>(stream);
     {
-        TraceScope tr("copy_probe_kernel", st);
         copy_probe_kernel<<<dim3((unsigned)blocks), dim3(kProbeThreads), 0, st>>>(static_cast<const vec16*>(src),
                                                                                    static_cast<vec16*>(dst), n_vec);
     }
-    return check_launch(fn, "copy_probe_kernel");
+    return hipGetLastError() == hipSuccess ? TAMOE_BENCH_OK : TAMOE_BENCH_HIP_ERROR;
 }

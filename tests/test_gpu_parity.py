@@ -112,20 +112,25 @@ def check_combine(y_gpu: np.ndarray, y_exact: np.ndarray, y_ref: np.ndarray, mag
         assert (np.abs(yv - y_exact) <= 1e-5 * np.maximum(np.abs(y_exact), mag)).all()
 
 
-def gpu_path(T, wl_like, x_np, w_np, penalty, cap, want_logits=True):
-    """Runs gate -> losses -> dispatch -> combine (identity expert) through the C ABI."""
+def gpu_path(T, wl_like, x_np, w_np, penalty, cap, want_logits=True, fused=False):
+    """Runs gate -> losses -> dispatch -> combine (identity expert) through the C ABI: the separate
+    entry points, or (fused) tamoe_gate_dispatch for everything up to the send buffer."""
     dt = wl_like["dtype"]
     N, P, k = wl_like["N"], wl_like["P"], wl_like["k"]
     x = to_dev(x_np, dt)
     w = to_dev(w_np, dt)
     S, d = x.shape
     ws = T.workspace(S, d, N, P, k, dt)
-    g = T.gate(x, w, P, k, want_logits=want_logits, ws=ws)
     pen = torch.from_numpy(penalty.astype(np.float32)).cuda()
     capd = torch.from_numpy(cap.astype(np.int32)).cuda()
-    l_topo = T.aux_loss(g["m"], g["c_expert"], pen, P, S) if S > 0 else None
+    if fused:
+        g = dsp = T.gate_dispatch(x, w, P, k, pen, capd, want_logits=want_logits, ws=ws)
+        l_topo = g["loss"] if S > 0 else None
+    else:
+        g = T.gate(x, w, P, k, want_logits=want_logits, ws=ws)
+        l_topo = T.aux_loss(g["m"], g["c_expert"], pen, P, S) if S > 0 else None
+        dsp = T.dispatch(x, g["topk_idx"], capd, N, P, ws=ws)
     l_aux = T.aux_loss(g["m"], g["c_expert"], None, P, S) if S > 0 else None
-    dsp = T.dispatch(x, g["topk_idx"], capd, N, P, ws=ws)
     torch.cuda.synchronize()
     K = int(dsp["expert_offset"][-1].item())
     y = T.combine(dsp["send"], K, dsp["slot"], g["topk_w"], d=d)
@@ -188,6 +193,20 @@ def full_parity(T, oracle, spec, x_np, w_np, penalty, cap, sample=None):
         tol = 1e-3 if dt != W.F32 else 1e-5
         assert g["l_topo"] == pytest.approx(own["l_topo"], rel=tol)
         assert g["l_aux"] == pytest.approx(own["l_aux"], rel=tol)
+
+    # The fused entry point (gate, loss and dispatch in three launches): what is decided from the scores
+    # must be the bits of the separate calls, which were just checked against the oracle; the two sums
+    # that it folds in another fixed order (m, the loss) are compared with the oracle directly.
+    f = gpu_path(T, spec, x_np, w_np, penalty, cap, fused=True)
+    for key in ("logits", "topk_idx", "topk_w", "c_expert", "c_device", "slot", "kept_expert", "expert_offset",
+                "send_count_dev", "y"):
+        np.testing.assert_array_equal(f[key], g[key], err_msg=f"fused {key}")
+    assert f["K"] == g["K"]
+    assert torch.equal(f["send_t"][: f["K"]].view(torch.uint8), g["send_t"][: g["K"]].view(torch.uint8))
+    np.testing.assert_allclose(f["m"], ref["m"], rtol=1e-5, atol=1e-12)
+    if S > 0:
+        assert f["l_topo"] == pytest.approx(ref["l_topo"], rel=1e-5)
+        assert f["l_aux"] == pytest.approx(ref["l_aux"], rel=1e-5)
     return g, ref
 
 
@@ -297,6 +316,7 @@ def test_eight_wavefront_gate_shapes(T, oracle, dtype, d, N, P, k):
     (W.BF16, 1000, 64, 128, 64, 8, 1.0),   # k at the limit, N at the limit
     (W.BF16, 2500, 264, 96, 8, 2, 2.0),    # several count tiles, ragged end
     (W.BF16, 70000, 16, 32, 4, 1, 1.1),    # many tokens, tiny rows
+    (W.BF16, 70001, 1024, 96, 8, 3, 0.9),  # more than 128 MiB of x: the fused call writes slots in a kernel of their own
     (W.F16, 33, 72, 5, 5, 2, 1.0),         # half precision: ragged tile, K tail, odd N
     (W.F16, 2500, 264, 96, 8, 2, 2.0),
     (W.F16, 1000, 64, 128, 64, 8, 1.0),
@@ -360,6 +380,12 @@ def test_empty_input(T):
     assert (g["m"] == 0).all()
     assert dsp["kept_expert"].sum().item() == 0 and (dsp["expert_offset"] == 0).all()
     assert dsp["send_count_dev"].sum().item() == 0 and y.shape == (0, d)
+    pen = torch.full((N,), 1.0 / N, device="cuda")
+    f = T.gate_dispatch(x, w, P, k, pen, cap)
+    torch.cuda.synchronize()
+    assert f["c_expert"].sum().item() == 0 and (f["m"] == 0).all() and f["loss"].item() == 0.0
+    assert f["kept_expert"].sum().item() == 0 and (f["expert_offset"] == 0).all()
+    assert f["send_count_dev"].sum().item() == 0 and f["c_device"].sum().item() == 0
 
 
 # ---------------------------------------------------------------------------
@@ -489,36 +515,46 @@ def test_aux_loss_closed_forms_on_device(T):
 
 
 # ---------------------------------------------------------------------------
-# bench aids: kernel trace and copy probe
+# measurement aids: the library's kernel trace, the benchmark's yardstick kernels
 # ---------------------------------------------------------------------------
-def test_trace_and_copy_probe(T):
-    src = torch.arange(1 << 20, dtype=torch.int32, device="cuda")
-    dst = torch.zeros_like(src)
+def test_kernel_trace_brackets_launches(T):
+    w_in = torch.rand((4096, 2), device="cuda") + 0.1
+    out = torch.empty_like(w_in)
     T.tamoe_trace_start(8)
     for _ in range(3):
-        T.tamoe_copy_probe(src, dst)
+        T.tamoe_renorm_topk(w_in, out)
     n = T.tamoe_trace_stop()
     assert n == 3
     for i in range(n):
         name, ms = T.tamoe_trace_get(i)
-        assert name == "copy_probe_kernel" and 0.0 < ms < 50.0
-    assert torch.equal(src, dst)
+        assert name == "renorm_topk_kernel" and 0.0 < ms < 50.0
     # a filter on another kernel's name records nothing; clearing it records again
     T.tamoe_trace_filter("combine_kernel")
     T.tamoe_trace_start(8)
-    T.tamoe_copy_probe(src, dst)
+    T.tamoe_renorm_topk(w_in, out)
     assert T.tamoe_trace_stop() == 0
     T.tamoe_trace_filter(None)
     T.tamoe_trace_start(1)
-    T.tamoe_copy_probe(src, dst)
-    T.tamoe_copy_probe(src, dst)            # beyond the capacity: not recorded, still executed
+    T.tamoe_renorm_topk(w_in, out)
+    T.tamoe_renorm_topk(w_in, out)            # beyond the capacity: not recorded, still executed
     assert T.tamoe_trace_stop() == 1
     T.tamoe_trace_clear()
     with pytest.raises(T.TamoeError):
         T.tamoe_trace_get(0)
 
 
-def test_step_can_be_captured_in_a_graph(T, oracle):
+def test_bench_copy_probe_copies():
+    from paper_2302_09915_amd import bench_aids as B
+
+    src = torch.arange(1 << 20, dtype=torch.int32, device="cuda")
+    dst = torch.zeros_like(src)
+    B.copy_probe(src, dst)
+    torch.cuda.synchronize()
+    assert torch.equal(src, dst)
+
+
+@pytest.mark.parametrize("fused", [False, True])
+def test_step_can_be_captured_in_a_graph(T, oracle, fused):
     """The library only enqueues kernels on the given stream (no allocation, no memset), so a whole
     step replays from a HIP graph; every replay must reproduce the eager result."""
     wl = W.WORKLOADS["small"]
@@ -552,6 +588,14 @@ def test_step_can_be_captured_in_a_graph(T, oracle):
         T.tamoe_dispatch(xin, b["topk_idx"], cap_d, N, P, b["send"], b["slot"], b["kept"], b["off"], b["scd"], ws)
         T.tamoe_combine(b["send"], S * k, b["slot"], b["topk_w"], b["y"])
 
+    def fused_step(xin):
+        b = bufs
+        T.tamoe_gate_dispatch(xin, w, P, k, pen_d, cap_d, None, b["topk_idx"], b["topk_w"], b["m"], b["c_expert"],
+                              b["c_device"], b["loss"], b["send"], b["slot"], b["kept"], b["off"], b["scd"], ws)
+        T.tamoe_combine(b["send"], S * k, b["slot"], b["topk_w"], b["y"])
+
+    if fused:
+        step = fused_step
     x_in = x.clone()
     step(x_in)
     torch.cuda.synchronize()
@@ -580,23 +624,25 @@ def test_step_can_be_captured_in_a_graph(T, oracle):
     assert torch.equal(bufs["c_expert"], eager["c_expert"])
 
 
-def test_mix_probe_moves_the_rows_it_is_told_to(T):
+def test_bench_mix_probe_moves_the_rows_it_is_told_to():
+    from paper_2302_09915_amd import bench_aids as B
+
     rows, d = 300, 512                                   # 1 KiB rows of bf16
     a = torch.randn((rows, d), device="cuda").to(torch.bfloat16)
     perm = torch.randperm(2 * rows, device="cuda").to(torch.int32)
     r0, r1 = perm[:rows].contiguous(), perm[rows:].contiguous()
     r1[7] = -1                                          # skipped
     b = torch.zeros((2 * rows, d), dtype=torch.bfloat16, device="cuda")
-    T.tamoe_mix_probe(a, b, r0, r1, 1)
+    B.mix_probe(a, b, r0, r1, 1)
     torch.cuda.synchronize()
     ai, bi = a.view(torch.int16), b.view(torch.int16)
     assert torch.equal(bi[r0.long()], ai)
     keep = r1 >= 0
     assert torch.equal(bi[r1[keep].long()], ai[keep])
     out = torch.empty_like(a)
-    T.tamoe_mix_probe(b, out, r0, r1, 2)
+    B.mix_probe(b, out, r0, r1, 2)
     torch.cuda.synchronize()
     expect = torch.where(keep[:, None], torch.zeros_like(ai), ai)   # x ^ x = 0 where both rows exist
     assert torch.equal(out.view(torch.int16), expect)
-    with pytest.raises(T.TamoeError):
-        T.tamoe_mix_probe(a[:, :100].contiguous(), b[:, :100].contiguous(), r0, r1, 1)
+    with pytest.raises(RuntimeError):
+        B.mix_probe(a[:, :100].contiguous(), b[:, :100].contiguous(), r0, r1, 1)
