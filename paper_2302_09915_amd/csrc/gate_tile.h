@@ -24,11 +24,27 @@ __device__ __forceinline__ int expert_of(int nb, int v, int half) {
     return nb * 32 + ((v >> 2) << 3) + (half << 2) + (v & 3);
 }
 
-// value of lane (lane ^ MASK) within each half of the wavefront (MASK < 32), through the
-// LDS crossbar without touching LDS memory
+// value of lane (lane ^ MASK), MASK < 32.  Masks 1, 2, 4, 8 stay inside a row of 16 lanes and are
+// composed from the data-parallel lane permutations of the vector unit, which cost an instruction
+// or two and no wait: 1 and 2 are quad permutations, 4 = reverse within 8 lanes then reverse
+// within 4, 8 = reverse within 16 then reverse within 8.  Mask 16 goes through the LDS crossbar
+// (ds_swizzle), whose result has to be waited for like an LDS read.
 template <int MASK>
 __device__ __forceinline__ float swizzle_xor(float v) {
-    return __int_as_float(__builtin_amdgcn_ds_swizzle(__float_as_int(v), (MASK << 10) | 0x1f));
+    const int x = __float_as_int(v);
+    if constexpr (MASK == 1) {
+        return __int_as_float(__builtin_amdgcn_update_dpp(0, x, 0xB1, 0xf, 0xf, true));    // quad_perm [1,0,3,2]
+    } else if constexpr (MASK == 2) {
+        return __int_as_float(__builtin_amdgcn_update_dpp(0, x, 0x4E, 0xf, 0xf, true));    // quad_perm [2,3,0,1]
+    } else if constexpr (MASK == 4) {
+        const int h = __builtin_amdgcn_update_dpp(0, x, 0x141, 0xf, 0xf, true);            // row_half_mirror: i ^ 7
+        return __int_as_float(__builtin_amdgcn_update_dpp(0, h, 0x1B, 0xf, 0xf, true));    // quad_perm [3,2,1,0]: ^ 3
+    } else if constexpr (MASK == 8) {
+        const int r = __builtin_amdgcn_update_dpp(0, x, 0x140, 0xf, 0xf, true);            // row_mirror: i ^ 15
+        return __int_as_float(__builtin_amdgcn_update_dpp(0, r, 0x141, 0xf, 0xf, true));   // row_half_mirror: ^ 7
+    } else {
+        return __int_as_float(__builtin_amdgcn_ds_swizzle(x, (MASK << 10) | 0x1f));
+    }
 }
 
 // One level of a transposed butterfly over the 32 token lanes: lanes that differ in bit S
@@ -281,15 +297,19 @@ __device__ __forceinline__ void select_tile(float (&sc)[NB][16], int lane, int64
         }
     }
 
-    // softmax: the first pick is the row maximum.  exp(t) = 2^(t * log2 e) on the hardware
-    // exponential; for t in [-100, 0] the product's rounding keeps the relative error below 1e-5.
+    // softmax: the first pick is the row maximum.  exp(l - max) = 2^(l*log2(e) - max*log2(e)) on the
+    // hardware exponential, one fused multiply-add per score.  The rounding of the product max*log2(e)
+    // shifts every exponent of the row by the same amount and cancels in the quotient; what is left is
+    // the rounding of the fused operation, below 1e-5 relative for differences down to -100.
+    constexpr float kLog2e = 1.44269504088896340736f;
     const float mx = sel_v[0];
+    const float shift = -(mx * kLog2e);
     float part = 0.f;
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
-            sc[nb][v] = __builtin_amdgcn_exp2f((sc[nb][v] - mx) * 1.44269504088896340736f);
+            sc[nb][v] = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[nb][v], kLog2e, shift));
             part += sc[nb][v];
         }
     const float den = part + __shfl_xor(part, 32);
@@ -300,7 +320,7 @@ __device__ __forceinline__ void select_tile(float (&sc)[NB][16], int lane, int64
         for (int j = 0; j < TAMOE_MAX_K; ++j) {
             if (j < k) {
                 topk_idx[token * k + j] = sel_i[j];
-                topk_w[token * k + j] = __builtin_amdgcn_exp2f((sel_v[j] - mx) * 1.44269504088896340736f) / den;
+                topk_w[token * k + j] = __builtin_amdgcn_exp2f(__builtin_fmaf(sel_v[j], kLog2e, shift)) / den;
             }
         }
     }
@@ -310,18 +330,23 @@ __device__ __forceinline__ void select_tile(float (&sc)[NB][16], int lane, int64
     // capacity-limited slot assignment needs from the gate.  Both halves hold the same selection.
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");   // the zeroes above before the atomics
     const int r_tok = lane & 31;
+    constexpr int kExpertBits = NB == 1 ? 5 : NB == 2 ? 6 : 7;   // experts < NB * 32
 #pragma unroll
     for (int j = 0; j < TAMOE_MAX_K; ++j) {
         tp.expert[j] = -1;
         tp.rank[j] = 0;
         if (j < k) {
             const int mine = (token_ok && sel_i[j] >= 0 && sel_i[j] < N) ? sel_i[j] : -1;
-            int rank = 0;
+            // lanes (of the 32 token lanes; the upper half holds copies) with the same expert: one ballot
+            // per bit of the expert index, and the lane keeps the mask or its complement
+            uint32_t same = (uint32_t)__ballot(mine >= 0);
 #pragma unroll
-            for (int rr = 0; rr < 31; ++rr) {
-                const int other = __builtin_amdgcn_readlane(mine, rr);
-                rank += (rr < r_tok && other == mine) ? 1 : 0;
+            for (int b = 0; b < kExpertBits; ++b) {
+                const bool bit = (mine >> b) & 1;
+                const uint32_t with_bit = (uint32_t)__ballot(bit);
+                same &= bit ? with_bit : ~with_bit;
             }
+            const int rank = __popc(same & ((1u << r_tok) - 1u));
             tp.expert[j] = mine;
             tp.rank[j] = rank;
             if (half == 0 && mine >= 0) atomicAdd(&pairs_wave[j * ROWS + mine], 1);
