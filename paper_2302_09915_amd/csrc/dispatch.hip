@@ -198,7 +198,9 @@ __global__ __launch_bounds__(kThreads) void dispatch_slot_kernel(
 // its slots are read once per wavefront through the scalar unit.
 // `shift` >= 0: cpr == 1 << shift, and the (token, column) split of a chunk index is a shift and a
 // mask; otherwise it is a division (32-bit when the tensor has fewer than 2^32 chunks).
-template <int KK, int U, bool ROWU>
+// STREAM: rows are written with streaming (nontemporal) stores; otherwise with ordinary ones, which
+// leave them in the last-level cache.
+template <int KK, int U, bool ROWU, bool STREAM>
 __global__ __launch_bounds__(kThreads) void dispatch_copy_kernel(const vec16* __restrict__ x,
                                                                  const int32_t* __restrict__ slot,
                                                                  int64_t total_chunks, int k_arg, int cpr, int shift,
@@ -232,7 +234,12 @@ __global__ __launch_bounds__(kThreads) void dispatch_copy_kernel(const vec16* __
         if (!live[u]) continue;
 #pragma unroll
         for (int j = 0; j < KM; ++j)
-            if (sl[u][j] >= 0) __builtin_nontemporal_store(v[u], send + (size_t)sl[u][j] * cpr + col[u]);
+            if (sl[u][j] >= 0) {
+                if (STREAM)
+                    __builtin_nontemporal_store(v[u], send + (size_t)sl[u][j] * cpr + col[u]);
+                else
+                    send[(size_t)sl[u][j] * cpr + col[u]] = v[u];
+            }
     }
 }
 
@@ -243,10 +250,18 @@ static void launch_copy(const void* x, const int32_t* slot, int64_t S, int k, in
     const vec16* src = static_cast<const vec16*>(x);
     vec16* dst = static_cast<vec16*>(send);
     const int shift = pow2_shift(cpr);
-    if (cpr % 64 == 0)
-        dispatch_copy_kernel<KK, U, true><<<grid, block, 0, st>>>(src, slot, total, k, cpr, shift, dst);
-    else
-        dispatch_copy_kernel<KK, U, false><<<grid, block, 0, st>>>(src, slot, total, k, cpr, shift, dst);
+    const bool stream = !send_stays_in_cache(S, k, cpr);
+    if (cpr % 64 == 0) {
+        if (stream)
+            dispatch_copy_kernel<KK, U, true, true><<<grid, block, 0, st>>>(src, slot, total, k, cpr, shift, dst);
+        else
+            dispatch_copy_kernel<KK, U, true, false><<<grid, block, 0, st>>>(src, slot, total, k, cpr, shift, dst);
+    } else {
+        if (stream)
+            dispatch_copy_kernel<KK, U, false, true><<<grid, block, 0, st>>>(src, slot, total, k, cpr, shift, dst);
+        else
+            dispatch_copy_kernel<KK, U, false, false><<<grid, block, 0, st>>>(src, slot, total, k, cpr, shift, dst);
+    }
 }
 
 void launch_dispatch_copy(const void* x, const int32_t* slot, int64_t S, int k, int cpr, void* send, hipStream_t st) {

@@ -87,6 +87,14 @@ int run_select_stage(const char* fn, const float* logits, int64_t S, int N, int 
 int check_select_outputs(const char* fn, int64_t S, int32_t* topk_idx, float* topk_w, float* m, int32_t* c_expert,
                          int32_t* c_device, void* ws, size_t ws_bytes, const Workspace& lay);
 
+// Rows written by the scatter stay in the last-level cache (ordinary stores) when the whole send buffer
+// fits well inside its 256 MB, so that whoever reads them next (the exchange, a local expert, the
+// combine of an identity layer) finds them there; larger buffers are written with streaming stores,
+// which do not push the token matrix out of that cache while the scatter still reads it.  Measured:
+// GPT-MoE layer (64 MiB of rows) 62.2 -> 60.6 us per step, skewed 59.8 -> 55.9, large (1 GiB) 648 -> 661.
+constexpr int64_t kCacheResidentSendBytes = (int64_t)96 << 20;
+inline bool send_stays_in_cache(int64_t S, int k, int cpr) { return S * k * (int64_t)cpr * 16 <= kCacheResidentSendBytes; }
+
 // The scatter of tamoe_dispatch on a finished slot table: send[slot[t][j]] = x[t] for every slot >= 0.
 // cpr: 16-byte chunks per row.
 void launch_dispatch_copy(const void* x, const int32_t* slot, int64_t S, int k, int cpr, void* send, hipStream_t st);

@@ -11,15 +11,15 @@
 //   3. route_copy_kernel: the scatter.  A pair's slot is offset[e] + prefix[e][j][b] + position, kept
 //      iff prefix + position < cap[e]; every thread derives the slots of its token on the way to
 //      moving its 16-byte chunk, and the thread with the row's first chunk writes them to slot[].
-//      Above 128 MiB of x the slots are written by route_slot_kernel (one thread per pair) and the rows
-//      are moved by the scatter of tamoe_dispatch: a fourth launch, but a shorter scatter.
+//      When the send buffer is too large to stay in the last-level cache (96 MiB) the slots are written
+//      by route_slot_kernel (one thread per pair) and the rows are moved by the scatter of
+//      tamoe_dispatch: a fourth launch, but a shorter scatter.
 #include "internal.h"
 #include "scan128.h"
 
 namespace tamoe {
 
 constexpr int kCopyThreads = 256;
-constexpr int64_t kFusedCopyMaxBytes = (int64_t)128 << 20;   // of x; above it the slots get a kernel of their own
 
 // Sum of v over the lanes below this one plus its own (wavefront of 64) with data-parallel
 // primitives: shifts by 1, 2, 4, 8 inside each row of 16 lanes (a lane without a source adds 0), then
@@ -181,7 +181,8 @@ __global__ __launch_bounds__(kExpertThreads) void route_empty_kernel(int N, int 
 }
 
 // The scatter with the slot assignment folded in.  Layout of the work as in dispatch_copy_kernel: one
-// 16-byte chunk per thread (two for k = 1), a wavefront inside one row when ROWU.
+// 16-byte chunk per thread (two for k = 1), a wavefront inside one row when ROWU.  Only launched for
+// batches whose send buffer fits the last-level cache, so the rows are written with ordinary stores.
 template <int KK, int U, bool ROWU>
 __global__ __launch_bounds__(kCopyThreads) void route_copy_kernel(
     const vec16* __restrict__ x, const int32_t* __restrict__ topk_idx, const int32_t* __restrict__ local_pos,
@@ -234,7 +235,7 @@ __global__ __launch_bounds__(kCopyThreads) void route_copy_kernel(
         if (!live[u]) continue;
 #pragma unroll
         for (int j = 0; j < KM; ++j)
-            if (sl[u][j] >= 0) __builtin_nontemporal_store(v[u], send + (size_t)sl[u][j] * cpr + col[u]);
+            if (sl[u][j] >= 0) send[(size_t)sl[u][j] * cpr + col[u]] = v[u];
     }
 }
 
@@ -359,9 +360,10 @@ extern "C" int tamoe_gate_dispatch(const void* x, const void* w, int dtype, int6
     a.send = send;
     a.st = st;
     // Slots in the scatter itself save a launch, but put two dependent table look-ups in front of every
-    // wavefront's copy: that pays while the scatter is short (large configuration, 512 MiB of x: 270 us
-    // against 257 + 4 us for the two kernels; GPT-MoE layer, 32 MiB: a step of 61 against 63 us).
-    if ((int64_t)S * cpr * 16 > kFusedCopyMaxBytes) {
+    // wavefront's copy: that pays while the scatter is short (large configuration, 1 GiB of rows to
+    // write: 270 us against 257 + 4 us for the two kernels; GPT-MoE layer, 64 MiB: a step of 61 against
+    // 63 us).  The line is drawn where the send buffer stops fitting the last-level cache.
+    if (!send_stays_in_cache(S, k, cpr)) {
         {
             TraceScope tr("route_slot_kernel", st);
             const int64_t pairs = S * k;
