@@ -202,6 +202,28 @@ def test_device_entry_points_reject_bad_shapes_without_a_gpu(T):
            T.WORKSPACE_TOO_SMALL, "needed")
     status(L.tamoe_dispatch(one, one, one, 1, 1 << 30, 64, 8, 4, 2, one, one, one, one, one, one, big, None),
            T.UNSUPPORTED, "int32")
+    # dispatch with the built-in scratch: the same checks, and the size limit before anything else happens
+    status(L.tamoe_dispatch_static(one, one, None, 1, 64, 64, 8, 4, 2, one, one, one, one, one, None),
+           T.INVALID_ARG, "cap is NULL")
+    status(L.tamoe_dispatch_static(one, one, one, 1, 64, 64, 8, 4, 2, one, one, None, one, one, None),
+           T.INVALID_ARG, "kept_expert is NULL")
+    status(L.tamoe_dispatch_static(one, one, one, 1, 300 * 1024, 64, 128, 64, 8, one, one, one, one, one, None),
+           T.UNSUPPORTED, "built-in scratch")
+    # gate + loss + dispatch in one call
+    gd = lambda **kw: L.tamoe_gate_dispatch(
+        kw.get("x", one), one, kw.get("dtype", 1), kw.get("S", 64), kw.get("d", 64), kw.get("N", 8), 4, kw.get("k", 2),
+        None, kw.get("cap", one), None, one, one, one, one, one, kw.get("loss", one), kw.get("send", one), one, one,
+        kw.get("off", one), one, one, kw.get("ws_bytes", big), None)
+    status(gd(k=9), T.INVALID_ARG, "k = 9 exceeds N")
+    status(gd(N=6), T.INVALID_ARG, "not a multiple of P")
+    status(gd(d=60), T.UNSUPPORTED, "multiple of 16 bytes")
+    status(gd(x=None), T.INVALID_ARG, "x is NULL")
+    status(gd(cap=None), T.INVALID_ARG, "cap is NULL")
+    status(gd(send=None), T.INVALID_ARG, "send is NULL")
+    status(gd(off=None), T.INVALID_ARG, "expert_offset is NULL")
+    status(gd(loss=odd if False else ctypes.c_void_p(258)), T.INVALID_ARG, "loss is not 4-byte aligned")
+    status(gd(ws_bytes=16), T.WORKSPACE_TOO_SMALL, "workspace has 16 bytes")
+    status(gd(S=1 << 30), T.UNSUPPORTED, "int32")
     # combine
     status(L.tamoe_combine(one, 10, one, one, 1, 64, 64, 0, one, None), T.INVALID_ARG, "k = 0")
     status(L.tamoe_combine(one, 10, one, one, 1, 64, 64, 2, None, None), T.INVALID_ARG, "y is NULL")
