@@ -24,6 +24,7 @@ def test_more_than_2_to_32_chunks(T):
     dev = torch.device("cuda:0")
     if torch.cuda.mem_get_info()[0] < 215 * 2 ** 30:
         pytest.skip("needs 215 GiB of free device memory (three 64 GiB matrices)")
+    print("64 GiB case: dispatch on given routing", flush=True)
     S, d, N, P, k = (1 << 21) + 3, 16384, 8, 8, 1
     assert S * d * 2 // 16 > 1 << 32
     g = torch.Generator(device=dev)
@@ -77,5 +78,50 @@ def test_more_than_2_to_32_chunks(T):
         ref = torch.where(live[s0:s0 + n, None], ref, torch.zeros_like(ref))
         bad += int((ref.view(torch.int16) != y[s0:s0 + n].view(torch.int16)).any(dim=1).sum().item())
     assert bad == 0
-    del x, send, y
+    del y
+    torch.cuda.empty_cache()
+
+    # The gate and the fused call on the same 64 GiB matrix: tamoe_gate_dispatch must give the bits of
+    # tamoe_gate + tamoe_dispatch (whose slot logic was checked above), and the gate's scores must agree
+    # with a library matrix product on a sample of rows.
+    print("64 GiB case: gate, then the fused call against the separate calls", flush=True)
+    N2, k2 = 8, 2
+    wg = (torch.randn((N2, d), generator=g, device=dev, dtype=torch.float32) / d ** 0.5).to(torch.bfloat16)
+    cap2 = torch.full((N2,), S // 6, dtype=torch.int32, device=dev)      # below the mean load 2S/8: drops
+    ws2 = T.workspace(S, d, N2, P, k2, T.BF16, dev)
+    sep = T.gate(x, wg, P, k2, want_logits=True, ws=ws2)
+    rows = torch.randint(0, S, (4096,), generator=g, device=dev)
+    ref = x[rows].float() @ wg.float().t()
+    assert (sep["logits"][rows] - ref).abs().max().item() <= 1e-3 * ref.abs().max().item()
+    assert int(sep["c_expert"].sum().item()) == S * k2
+    del send, sep
+    torch.cuda.empty_cache()
+    # rows of d/2 elements (the first half of every row of x) keep two send buffers of k = 2 within the
+    # memory of the 64 GiB case; 8193 gate workgroups: the per-expert scans of the fused call run over
+    # several pieces
+    xh = x.view(S * 2, d // 2)[::2].contiguous()
+    del x
+    torch.cuda.empty_cache()
+    wh = wg[:, : d // 2].contiguous()
+    slot_a = torch.empty((S, k2), dtype=torch.int32, device=dev)
+    kept_a, off_a, scd_a = torch.empty_like(kept), torch.empty_like(off), torch.empty_like(scd)
+    send_a = torch.empty((S * k2, d // 2), dtype=torch.bfloat16, device=dev)
+    sep = T.gate(xh, wh, P, k2, want_logits=False, ws=ws2)
+    T.tamoe_dispatch(xh, sep["topk_idx"], cap2, N2, P, send_a, slot_a, kept_a, off_a, scd_a, ws2, None)
+    pen = torch.full((N2,), 1.0 / N2, device=dev)
+    fz = T.gate_dispatch(xh, wh, P, k2, pen, cap2, want_logits=False, ws=ws2)
+    torch.cuda.synchronize()
+    for name, a, b in (("topk_idx", sep["topk_idx"], fz["topk_idx"]), ("topk_w", sep["topk_w"], fz["topk_w"]),
+                       ("c_expert", sep["c_expert"], fz["c_expert"]), ("slot", slot_a, fz["slot"]),
+                       ("kept", kept_a, fz["kept_expert"]), ("off", off_a, fz["expert_offset"]),
+                       ("scd", scd_a, fz["send_count_dev"])):
+        assert torch.equal(a, b), name
+    K2 = int(off_a[-1].item())
+    assert 0 < K2 < S * k2                                                # capacity dropped some pairs
+    bad = 0
+    for r0 in range(0, K2, 1 << 15):
+        r1 = min(K2, r0 + (1 << 15))
+        bad += int((send_a[r0:r1].view(torch.int16) != fz["send"][r0:r1].view(torch.int16)).any(dim=1).sum().item())
+    assert bad == 0
+    del xh, send_a, fz
     torch.cuda.empty_cache()
