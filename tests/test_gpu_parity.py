@@ -388,6 +388,46 @@ def test_empty_input(T):
     assert f["send_count_dev"].sum().item() == 0 and f["c_device"].sum().item() == 0
 
 
+@pytest.mark.parametrize("capv", [0, 1, 45, 10 ** 6])
+def test_fused_call_options(T, oracle, capv):
+    """tamoe_gate_dispatch without a penalty (the loss is then l_aux of Section 3.1), without a loss
+    pointer, and under capacities that keep nothing, one row, some rows, everything."""
+    S, d, N, P, k = 3001, 192, 48, 8, 2
+    rng = np.random.default_rng(capv + 3)
+    x_np = W.to_storage(rng.standard_normal((S, d)).astype(np.float32), W.BF16)
+    w_np = W.to_storage((rng.standard_normal((N, d)) / np.sqrt(d)).astype(np.float32), W.BF16)
+    cap = np.full(N, capv, dtype=np.int32)
+    if capv == 45:
+        cap[::5] = 0
+        cap[1::7] = 10 ** 6
+    x, w = to_dev(x_np, W.BF16), to_dev(w_np, W.BF16)
+    capd = torch.from_numpy(cap).cuda()
+    f = T.gate_dispatch(x, w, P, k, None, capd)
+    torch.cuda.synchronize()
+    ref = oracle.route_from_logits(f["logits"].cpu().numpy().astype(np.float64), k, P, np.full(N, 1.0 / N), cap)
+    assert f["loss"].item() == pytest.approx(ref["l_aux"], rel=1e-5)
+    np.testing.assert_array_equal(f["topk_idx"].cpu().numpy(), ref["topk_idx"])
+    np.testing.assert_array_equal(f["slot"].cpu().numpy(), ref["slot"])
+    np.testing.assert_array_equal(f["kept_expert"].cpu().numpy(), ref["kept"])
+    np.testing.assert_array_equal(f["expert_offset"].cpu().numpy(), ref["off"])
+    np.testing.assert_array_equal(f["send_count_dev"].cpu().numpy(), ref["send_count_dev"])
+    K = ref["K"]
+    assert K == {0: 0, 1: N, 10 ** 6: S * k}.get(capv, K)
+    np.testing.assert_array_equal(to_host(f["send"][:K], W.BF16), oracle.scatter(x_np, W.BF16, ref["slot"], K))
+    # no loss pointer: everything else as before
+    g = T.gate_dispatch(x, w, P, k, None, capd)
+    g["loss"].fill_(-7.0)
+    T.tamoe_gate_dispatch(x, w, P, k, None, capd, g["logits"], g["topk_idx"], g["topk_w"], g["m"], g["c_expert"],
+                          g["c_device"], None, g["send"], g["slot"], g["kept_expert"], g["expert_offset"],
+                          g["send_count_dev"], T.workspace(S, d, N, P, k, W.BF16))
+    torch.cuda.synchronize()
+    assert g["loss"].item() == -7.0
+    for key in ("topk_idx", "topk_w", "m", "c_expert", "c_device", "slot", "kept_expert", "expert_offset",
+                "send_count_dev"):
+        assert torch.equal(f[key], g[key]), key
+    assert torch.equal(f["send"][:K].view(torch.int16), g["send"][:K].view(torch.int16))
+
+
 # ---------------------------------------------------------------------------
 # selection stage fed given scores: ties, extreme values
 # ---------------------------------------------------------------------------
