@@ -123,7 +123,6 @@ static GateStats stats_in(void* ws, const Workspace& lay, int k, int64_t blocks)
     gs.m_part = reinterpret_cast<float*>(static_cast<char*>(ws) + lay.m_part);
     gs.tile_pairs = reinterpret_cast<int32_t*>(static_cast<char*>(ws) + lay.tile_pairs);
     gs.local_pos = reinterpret_cast<int32_t*>(static_cast<char*>(ws) + lay.local_pos);
-    gs.done = reinterpret_cast<uint32_t*>(static_cast<char*>(ws) + lay.done);
     gs.n_blocks = (int)blocks;
     gs.pitch = (int)pair_pitch(k, blocks);
     return gs;

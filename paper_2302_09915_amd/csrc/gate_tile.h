@@ -385,7 +385,6 @@ __device__ __forceinline__ void finish_block(const float (*m_w)[NB * 32], const 
                                              const TokenPairs& tp, int lane, int wave, int64_t token, bool token_ok,
                                              int N, int k, const GateStats& gs) {
     constexpr int ROWS = NB * 32;
-    if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) *gs.done = 0u;
     __syncthreads();
     if ((lane >> 5) == 0 && token_ok) {
 #pragma unroll

@@ -54,8 +54,6 @@ Workspace workspace_layout(int64_t S, int N, int k, int dtype) {
     off = align_up(off + (size_t)pair_pitch(k, (int64_t)gb) * N * sizeof(int32_t), 256);
     w.local_pos = off;
     off = align_up(off + (size_t)S * k * sizeof(int32_t), 256);
-    w.done = off;
-    off += 256;
     w.tile_count = off;
     off = align_up(off + (size_t)k * count_tiles(S) * N * sizeof(int32_t), 256);
     // last, so that the other offsets do not depend on the storage type; sized for the largest batch

@@ -52,7 +52,6 @@ struct Workspace {
     size_t tile_pairs;  // int32  [N][pair_pitch]         gate: pairs per (expert; choice, workgroup), then their
                         //                                exclusive prefix in priority order
     size_t local_pos;   // int32  [S][k]                  gate: position of a pair among those of its workgroup
-    size_t done;        // uint32 [1]                     ticket counter, reset by every gate launch
     size_t tile_count;  // int32  [k][count_tiles][N]     dispatch on given routing: pair counts, then their prefix
     size_t part_logits; // float  [kMaxKSplits][S][N]     partial scores of a K-split gate (small S only)
     size_t total;
@@ -66,8 +65,6 @@ struct GateStats {
     float* m_part;        // [N][n_blocks]      sums of gate probabilities per workgroup
     int32_t* tile_pairs;  // [N][pitch]         pairs per (expert; choice j, workgroup b) at [e*pitch + j*n_blocks + b]
     int32_t* local_pos;   // [S][k]             earlier pairs of the same workgroup with the same expert and choice
-    uint32_t* done;       // [1]                set to zero by the gate's first workgroup (a ticket counter for
-                          //                    the kernel behind it)
     int n_blocks;
     int pitch;
 };

@@ -6,16 +6,18 @@
 //   1. the gate kernel (gate_tile.h) leaves, besides the selection, per gate workgroup b the number of
 //      pairs per (expert e, choice j) and for every pair its position among the pairs of (b, e, j);
 //   2. route_expert_kernel, one workgroup per expert: mean probability, count, the exclusive prefix of
-//      the expert's pair counts in priority order (choice-major, then token order), kept rows; the
-//      workgroup that finishes last adds expert offsets, rows per destination device and the loss;
+//      the expert's pair counts in priority order (choice-major, then token order), kept rows;
 //   3. route_copy_kernel: the scatter.  A pair's slot is offset[e] + prefix[e][j][b] + position, kept
-//      iff prefix + position < cap[e]; every thread derives the slots of its token on the way to
-//      moving its 16-byte chunk, and the thread with the row's first chunk writes them to slot[].
+//      iff prefix + position < cap[e]; offset[e] is the sum of the kept rows of the experts before e,
+//      which every wavefront takes from the N kept counts by a scan of its own (two loads and a dozen
+//      lane shifts: cheaper than one more pass over the experts in front of the scatter); every
+//      thread derives the slots of its token on the way to moving its 16-byte chunk, and the thread
+//      with the row's first chunk writes them to slot[].  The first workgroup also writes what
+//      describes the layer as a whole: expert offsets, rows per destination device, the loss.
 //      When the send buffer is too large to stay in the last-level cache (96 MiB) the slots are written
-//      by route_slot_kernel (one thread per pair) and the rows are moved by the scatter of
-//      tamoe_dispatch: a fourth launch, but a shorter scatter.
+//      by route_slot_kernel (one thread per pair, same offsets, same first workgroup) and the rows are
+//      moved by the scatter of tamoe_dispatch: a fourth launch, but a shorter scatter.
 #include "internal.h"
-#include "scan128.h"
 
 namespace tamoe {
 
@@ -38,38 +40,33 @@ __device__ __forceinline__ int32_t wave_inclusive_scan(int32_t v) {
 // place), its total, kept rows and mean probability.  A single workgroup for all experts would be a
 // chain of memory round trips through one compute unit's few outstanding misses (measured: 27 us for
 // 640 KiB on the large configuration); spread over N compute units each has two kilobytes to fetch.
-// What needs every expert (offsets, rows per device, the loss) is done by the workgroup that
-// finishes last: each publishes its three numbers, then takes a ticket from a counter that the gate
-// kernel has reset; no workgroup waits for another.
+// Nothing here needs another expert: what does (offsets, rows per device, the loss) is left to the
+// kernel that follows, which has to wait for this one anyway.
 constexpr int kExpertThreads = 256;
 
-template <typename V>
-__device__ __forceinline__ void publish(V* p, V v) {
-    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-template <typename V>
-__device__ __forceinline__ V observe(const V* p) {
-    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-
 __global__ __launch_bounds__(kExpertThreads) void route_expert_kernel(
-    const float* __restrict__ m_part, int32_t* __restrict__ tile_pairs, int n_blocks, int entries, int pitch, int N,
-    int P, int64_t S, const float* __restrict__ penalty, float loss_scale, const int32_t* __restrict__ cap,
-    float* m, int32_t* c_expert, int32_t* __restrict__ c_device, float* __restrict__ loss, int32_t* kept_expert,
-    int32_t* __restrict__ expert_offset, int32_t* __restrict__ send_count_dev, uint32_t* done_counter) {
+    const float* __restrict__ m_part, int32_t* __restrict__ tile_pairs, int n_blocks, int entries, int pitch,
+    int64_t S, const int32_t* __restrict__ cap, float* __restrict__ m, int32_t* __restrict__ c_expert,
+    int32_t* __restrict__ kept_expert) {
     constexpr int kWaves = kExpertThreads / 64;
     __shared__ int32_t wave_cnt[kWaves];
     __shared__ float wave_sum[kWaves];
-    __shared__ int is_last;
-    __shared__ int32_t total[TAMOE_MAX_EXPERTS];
-    __shared__ int32_t kept[TAMOE_MAX_EXPERTS];
-    __shared__ int32_t off[TAMOE_MAX_EXPERTS + 1];
-    __shared__ int32_t tmp[2 * 128];
-    __shared__ float term[TAMOE_MAX_EXPERTS];
 
     const int e = blockIdx.x;
     const int tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6;
+
+    // probability sums of this expert: thread-wise over ascending pieces, then lanes, then wavefronts
+    // (requested first: they need nothing from the scan below)
+    float acc = 0.f;
+    const float* mrow = m_part + (size_t)e * n_blocks;
+    for (int q0 = 0; q0 < n_blocks; q0 += 4 * kExpertThreads) {
+        const int q = q0 + 4 * tid;
+        // rows of n_blocks floats are not 16-byte aligned in general
+        const float x0 = q < n_blocks ? mrow[q] : 0.f, x1 = q + 1 < n_blocks ? mrow[q + 1] : 0.f;
+        const float x2 = q + 2 < n_blocks ? mrow[q + 2] : 0.f, x3 = q + 3 < n_blocks ? mrow[q + 3] : 0.f;
+        acc += (x0 + x1) + (x2 + x3);
+    }
 
     // pair counts of this expert, 1024 entries (16 bytes per thread) at a time
     int32_t* row = tile_pairs + (size_t)e * pitch;
@@ -97,16 +94,6 @@ __global__ __launch_bounds__(kExpertThreads) void route_expert_kernel(
         __syncthreads();
     }
 
-    // probability sums of this expert: thread-wise over ascending pieces, then lanes, then wavefronts
-    float acc = 0.f;
-    const float* mrow = m_part + (size_t)e * n_blocks;
-    for (int q0 = 0; q0 < n_blocks; q0 += 4 * kExpertThreads) {
-        const int q = q0 + 4 * tid;
-        // rows of n_blocks floats are not 16-byte aligned in general
-        const float x0 = q < n_blocks ? mrow[q] : 0.f, x1 = q + 1 < n_blocks ? mrow[q + 1] : 0.f;
-        const float x2 = q + 2 < n_blocks ? mrow[q + 2] : 0.f, x3 = q + 3 < n_blocks ? mrow[q + 3] : 0.f;
-        acc += (x0 + x1) + (x2 + x3);
-    }
 #pragma unroll
     for (int sft = 32; sft > 0; sft >>= 1) acc += __shfl_xor(acc, sft);
     if (lane == 0) wave_sum[wave] = acc;
@@ -115,33 +102,81 @@ __global__ __launch_bounds__(kExpertThreads) void route_expert_kernel(
     if (tid == 0) {
         const float sum = (wave_sum[0] + wave_sum[1]) + (wave_sum[2] + wave_sum[3]);
         const int32_t lim = cap[e] < 0 ? 0 : cap[e];
-        publish(&m[e], S > 0 ? sum / (float)S : 0.f);
-        publish(&c_expert[e], carry);
-        publish(&kept_expert[e], carry < lim ? carry : lim);
-        __threadfence();                                      // the three numbers before the ticket
-        const uint32_t ticket = atomicAdd(done_counter, 1u);
-        is_last = ticket == (uint32_t)N - 1u;
+        m[e] = S > 0 ? sum / (float)S : 0.f;
+        c_expert[e] = carry;
+        kept_expert[e] = carry < lim ? carry : lim;
     }
-    __syncthreads();
-    if (!is_last) return;
+}
 
-    // ---- the last workgroup: what needs every expert ----
-    __threadfence();                                          // the ticket before the others' numbers
-    if (tid < TAMOE_MAX_EXPERTS) {
-        int32_t c = 0, kp = 0;
-        float t = 0.f;
-        if (tid < N) {
-            c = observe(&c_expert[tid]);
-            kp = observe(&kept_expert[tid]);
-            t = observe(&m[tid]) * (float)c * (penalty != nullptr ? penalty[tid] : 1.f);
-        }
-        total[tid] = c;
-        kept[tid] = kp;
-        term[tid] = t;
+// offset[e] = kept rows of the experts before e, for the (at most two) experts a lane is asked about:
+// every wavefront scans the N <= 128 kept counts by itself.  Called by all 64 lanes.
+struct WaveOffsets {
+    int32_t ex0, ex1;   // exclusive prefix at expert lane, lane + 64
+};
+// The lane's two kept counts: requested at the top of a kernel, scanned (wave_offsets) only where the
+// first offset is needed, so that the round trip runs beside the kernel's other loads.
+struct KeptPair {
+    int32_t k0, k1;
+};
+__device__ __forceinline__ KeptPair load_kept(const int32_t* __restrict__ kept_expert, int N) {
+    static_assert(TAMOE_MAX_EXPERTS <= 128, "two experts per lane");
+    const int lane = threadIdx.x & 63;
+    return KeptPair{lane < N ? kept_expert[lane] : 0, lane + 64 < N ? kept_expert[lane + 64] : 0};
+}
+__device__ __forceinline__ WaveOffsets wave_offsets(const KeptPair& kp) {
+    const int32_t i0 = wave_inclusive_scan(kp.k0);
+    const int32_t i1 = wave_inclusive_scan(kp.k1) + __builtin_amdgcn_readlane(i0, 63);
+    return WaveOffsets{i0 - kp.k0, i1 - kp.k1};
+}
+// e in [0, 128).  UNIFORM: e is the same in every lane (read through the scalar unit, no lane exchange);
+// otherwise any value per lane, and all 64 lanes must take part.
+template <bool UNIFORM>
+__device__ __forceinline__ int32_t offset_of(const WaveOffsets& o, int e) {
+    if constexpr (UNIFORM) {
+        const int eu = __builtin_amdgcn_readfirstlane(e);
+        const int32_t lo = __builtin_amdgcn_readlane(o.ex0, eu & 63), hi = __builtin_amdgcn_readlane(o.ex1, eu & 63);
+        return eu < 64 ? lo : hi;
+    } else {
+        const int32_t lo = __shfl(o.ex0, e & 63), hi = __shfl(o.ex1, e & 63);
+        return e < 64 ? lo : hi;
+    }
+}
+
+// What describes the layer as a whole, by one workgroup of kCopyThreads threads that does nothing else
+// (every thread calls): expert offsets (Section 4.3: what the size exchange carries), rows and pairs per
+// destination device, the loss.  N <= 128 values: the first wavefront holds two experts per lane, scans
+// and sums them with lane operations (fixed order), and hands offsets and counts to the threads that
+// write the per-device numbers through LDS.
+__device__ __forceinline__ void route_layer_outputs(const float* __restrict__ m, const int32_t* __restrict__ c_expert,
+                                                    const int32_t* __restrict__ kept_expert,
+                                                    const float* __restrict__ penalty, float loss_scale, int N, int P,
+                                                    int32_t* __restrict__ c_device, float* __restrict__ loss,
+                                                    int32_t* __restrict__ expert_offset,
+                                                    int32_t* __restrict__ send_count_dev) {
+    __shared__ int32_t total[TAMOE_MAX_EXPERTS];
+    __shared__ int32_t off[TAMOE_MAX_EXPERTS + 1];
+    const int tid = threadIdx.x;
+    if (tid < 64) {
+        const int e0 = tid, e1 = tid + 64;
+        const int32_t c0 = e0 < N ? c_expert[e0] : 0, c1 = e1 < N ? c_expert[e1] : 0;
+        const int32_t k0 = e0 < N ? kept_expert[e0] : 0, k1 = e1 < N ? kept_expert[e1] : 0;
+        float t0 = 0.f, t1 = 0.f;
+        if (e0 < N) t0 = m[e0] * (float)c0 * (penalty != nullptr ? penalty[e0] : 1.f);
+        if (e1 < N) t1 = m[e1] * (float)c1 * (penalty != nullptr ? penalty[e1] : 1.f);
+        const int32_t i0 = wave_inclusive_scan(k0);
+        const int32_t i1 = wave_inclusive_scan(k1) + __builtin_amdgcn_readlane(i0, 63);
+        total[e0] = c0;
+        total[e1] = c1;
+        off[e0] = i0 - k0;
+        off[e1] = i1 - k1;
+        if (e0 == N - 1) off[N] = i0;
+        if (e1 == N - 1) off[N] = i1;
+        float term = t0 + t1;
+#pragma unroll
+        for (int sft = 32; sft > 0; sft >>= 1) term += __shfl_xor(term, sft);
+        if (tid == 0 && loss != nullptr) loss[0] = term * loss_scale;
     }
     __syncthreads();
-    // sizes (Section 4.3: what the size exchange carries), counts per device, the loss
-    exclusive_scan_128(kept, off, tmp, N);
     if (tid <= N) expert_offset[tid] = off[tid];
     if (tid < P) {
         const int E = N / P;
@@ -150,15 +185,23 @@ __global__ __launch_bounds__(kExpertThreads) void route_expert_kernel(
         for (int q = 0; q < E; ++q) c += total[tid * E + q];
         c_device[tid] = c;
     }
-    for (int stride = TAMOE_MAX_EXPERTS / 2; stride > 0; stride >>= 1) {
-        if (tid < stride) term[tid] += term[tid + stride];
-        __syncthreads();
-    }
-    if (tid == 0 && loss != nullptr) loss[0] = term[0] * loss_scale;
 }
 
-// No tokens: every size, count and sum is zero (the gate kernel, which resets the ticket counter of
-// route_expert_kernel, does not run then).
+// Arguments of route_layer_outputs, handed through the kernels whose first workgroup calls it.
+struct LayerOutputs {
+    const float* m;
+    const int32_t* c_expert;
+    const int32_t* kept_expert;
+    const float* penalty;
+    float loss_scale;
+    int P;
+    int32_t* c_device;
+    float* loss;
+    int32_t* expert_offset;
+    int32_t* send_count_dev;
+};
+
+// No tokens: every size, count and sum is zero.
 __global__ __launch_bounds__(kExpertThreads) void route_empty_kernel(int N, int P, float* __restrict__ m,
                                                                     int32_t* __restrict__ c_expert,
                                                                     int32_t* __restrict__ c_device,
@@ -181,114 +224,163 @@ __global__ __launch_bounds__(kExpertThreads) void route_empty_kernel(int N, int 
 }
 
 // The scatter with the slot assignment folded in.  Layout of the work as in dispatch_copy_kernel: one
-// 16-byte chunk per thread (two for k = 1), a wavefront inside one row when ROWU.  Only launched for
-// batches whose send buffer fits the last-level cache, so the rows are written with ordinary stores.
+// 16-byte chunk per thread (two for k = 1), a wavefront inside one row when ROWU (its token's experts,
+// positions and table entries then go through the scalar unit).  Only launched for batches whose send
+// buffer fits the last-level cache, so the rows are written with ordinary stores.  Workgroup 0 writes
+// the layer's outputs and moves no rows: as part of a copying workgroup that tail would end after every
+// other workgroup of a short launch.
 template <int KK, int U, bool ROWU>
 __global__ __launch_bounds__(kCopyThreads) void route_copy_kernel(
     const vec16* __restrict__ x, const int32_t* __restrict__ topk_idx, const int32_t* __restrict__ local_pos,
-    const int32_t* __restrict__ tile_base, const int32_t* __restrict__ cap,
-    const int32_t* __restrict__ expert_offset, int64_t total_chunks, int k_arg, int cpr, int shift, int N,
-    int n_blocks, int pitch, int tile_shift, int32_t* __restrict__ slot, vec16* __restrict__ send) {
+    const int32_t* __restrict__ tile_base, const int32_t* __restrict__ cap, int64_t total_chunks, int k_arg, int cpr,
+    int shift, int N, int n_blocks, int pitch, int tile_shift, int32_t* __restrict__ slot, vec16* __restrict__ send,
+    const LayerOutputs lo) {
+    if (blockIdx.x == 0) {
+        route_layer_outputs(lo.m, lo.c_expert, lo.kept_expert, lo.penalty, lo.loss_scale, N, lo.P, lo.c_device, lo.loss,
+                            lo.expert_offset, lo.send_count_dev);
+        return;
+    }
     constexpr int KM = KK > 0 ? KK : TAMOE_MAX_K;
     const int k = KK > 0 ? KK : k_arg;
-    const int64_t base = (int64_t)blockIdx.x * (kCopyThreads * U) + threadIdx.x;
+    const int64_t base = (int64_t)(blockIdx.x - 1) * (kCopyThreads * U) + threadIdx.x;
+    const KeptPair kp = load_kept(lo.kept_expert, N);
     vec16 v[U];
-    int32_t sl[U][KM];
-    int col[U];
-    bool live[U];
+    int32_t e[U][KM], pos[U][KM];   // pos < 0: the pair is not kept
+    int col[U], tok[U];
+    bool live[U], inside[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
         const int64_t c = base + (int64_t)u * kCopyThreads;
+        inside[u] = c < total_chunks;
         live[u] = false;
         col[u] = 0;
-        if (c < total_chunks) {
-            int t;
-            split_chunk(c, total_chunks, cpr, shift, t, col[u]);
-            if (ROWU) t = __builtin_amdgcn_readfirstlane(t);
-            const int blk = t >> tile_shift;
-            int32_t e[KM], lp[KM];
+        tok[u] = 0;
 #pragma unroll
-            for (int j = 0; j < KM; ++j) {
-                e[j] = j < k ? topk_idx[(int64_t)t * k + j] : -1;
-                lp[j] = j < k ? local_pos[(int64_t)t * k + j] : 0;
-            }
+        for (int j = 0; j < KM; ++j) {
+            e[u][j] = 0;
+            pos[u][j] = -1;
+        }
+        if constexpr (ROWU) {   // the wavefront is inside or outside as a whole
+            inside[u] = __builtin_amdgcn_readfirstlane((int)inside[u]) != 0;
+            if (!inside[u]) continue;
+            inside[u] = true;
+        }
+        if (inside[u]) {
+            split_chunk(c, total_chunks, cpr, shift, tok[u], col[u]);
+            if (ROWU) tok[u] = __builtin_amdgcn_readfirstlane(tok[u]);
+        }
+        const int t = tok[u];
+        const int blk = t >> tile_shift;
+        int32_t lp[KM], first[KM], lim[KM];
+        bool valid[KM];
 #pragma unroll
-            for (int j = 0; j < KM; ++j) {
-                sl[u][j] = -1;
-                if (j < k && e[j] >= 0 && e[j] < N) {
-                    const int32_t pos = tile_base[(size_t)e[j] * pitch + (size_t)j * n_blocks + blk] + lp[j];
-                    const int32_t lim = cap[e[j]];
-                    if (pos < lim) sl[u][j] = expert_offset[e[j]] + pos;
-                }
-                live[u] |= sl[u][j] >= 0;
-            }
-            if (live[u]) v[u] = __builtin_nontemporal_load(x + c);
-            if (col[u] == 0) {
+        for (int j = 0; j < KM; ++j) {
+            e[u][j] = (inside[u] && j < k) ? topk_idx[(int64_t)t * k + j] : -1;
+            lp[j] = (inside[u] && j < k) ? local_pos[(int64_t)t * k + j] : 0;
+        }
+        // the table entries of all choices are requested together and unconditionally (expert 0 stands
+        // in for a missing one): behind a test each would be a memory round trip of its own
 #pragma unroll
-                for (int j = 0; j < KM; ++j)
-                    if (j < k) slot[(int64_t)t * k + j] = sl[u][j];
+        for (int j = 0; j < KM; ++j) {
+            valid[j] = e[u][j] >= 0 && e[u][j] < N;
+            e[u][j] = valid[j] ? e[u][j] : 0;
+            first[j] = 0;
+            lim[j] = 0;
+            if (j < k) {
+                first[j] = tile_base[(size_t)e[u][j] * pitch + (size_t)j * n_blocks + blk];
+                lim[j] = cap[e[u][j]];
             }
         }
+#pragma unroll
+        for (int j = 0; j < KM; ++j) {
+            const int32_t p = first[j] + lp[j];
+            if (valid[j] && p < lim[j]) pos[u][j] = p;
+            live[u] |= pos[u][j] >= 0;
+        }
+        if (live[u]) v[u] = __builtin_nontemporal_load(x + c);
     }
+    // every lane is back here: the scan and, without ROWU, the lane exchange of offset_of need them all
+    const WaveOffsets wo = wave_offsets(kp);
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-        if (!live[u]) continue;
+        int32_t sl[KM];
 #pragma unroll
-        for (int j = 0; j < KM; ++j)
-            if (sl[u][j] >= 0) send[(size_t)sl[u][j] * cpr + col[u]] = v[u];
+        for (int j = 0; j < KM; ++j) {
+            sl[j] = -1;
+            if (j < k) {
+                const int32_t off = offset_of<ROWU>(wo, e[u][j]);
+                if (pos[u][j] >= 0) sl[j] = off + pos[u][j];
+            }
+        }
+        if (inside[u] && col[u] == 0) {
+#pragma unroll
+            for (int j = 0; j < KM; ++j)
+                if (j < k) slot[(int64_t)tok[u] * k + j] = sl[j];
+        }
+        if (live[u]) {
+#pragma unroll
+            for (int j = 0; j < KM; ++j)
+                if (sl[j] >= 0) send[(size_t)sl[j] * cpr + col[u]] = v[u];
+        }
     }
 }
 
 // The slot of every pair by itself: one thread per pair.  For batches whose scatter is bound by
 // bandwidth, where the extra table lookups in front of every wavefront's copy would cost more than a
-// launch.
+// launch.  Workgroup 0 writes the layer's outputs instead.
 __global__ __launch_bounds__(kCopyThreads) void route_slot_kernel(
     const int32_t* __restrict__ topk_idx, const int32_t* __restrict__ local_pos,
-    const int32_t* __restrict__ tile_base, const int32_t* __restrict__ cap,
-    const int32_t* __restrict__ expert_offset, int64_t pairs, int k, int N, int n_blocks, int pitch, int tile_shift,
-    int32_t* __restrict__ slot) {
-    const int64_t p = (int64_t)blockIdx.x * kCopyThreads + threadIdx.x;
-    if (p >= pairs) return;
-    const int e = topk_idx[p];
-    const int32_t lp = local_pos[p];
-    const int64_t t = p / k;
-    const int j = (int)(p - t * k);
-    int32_t sl = -1;
-    if (e >= 0 && e < N) {
-        const int32_t pos = tile_base[(size_t)e * pitch + (size_t)j * n_blocks + (t >> tile_shift)] + lp;
-        if (pos < cap[e]) sl = expert_offset[e] + pos;
+    const int32_t* __restrict__ tile_base, const int32_t* __restrict__ cap, int64_t pairs, int k, int N, int n_blocks,
+    int pitch, int tile_shift, int32_t* __restrict__ slot, const LayerOutputs lo) {
+    if (blockIdx.x == 0) {
+        route_layer_outputs(lo.m, lo.c_expert, lo.kept_expert, lo.penalty, lo.loss_scale, N, lo.P, lo.c_device, lo.loss,
+                            lo.expert_offset, lo.send_count_dev);
+        return;
     }
-    slot[p] = sl;
+    const KeptPair kp = load_kept(lo.kept_expert, N);
+    const int64_t p = (int64_t)(blockIdx.x - 1) * kCopyThreads + threadIdx.x;
+    const bool inside = p < pairs;
+    const int e = inside ? topk_idx[p] : -1;
+    const int32_t lp = inside ? local_pos[p] : 0;
+    const bool valid = e >= 0 && e < N;
+    const int ee = valid ? e : 0;                  // both table entries requested together, unconditionally
+    const int64_t t = inside ? p / k : 0;
+    const int j = inside ? (int)(p - t * k) : 0;
+    const int32_t q = tile_base[(size_t)ee * pitch + (size_t)j * n_blocks + (t >> tile_shift)] + lp;
+    const int32_t pos = (valid && q < cap[ee]) ? q : -1;
+    const WaveOffsets wo = wave_offsets(kp);
+    const int32_t off = offset_of<false>(wo, valid ? e : 0);
+    if (inside) slot[p] = pos >= 0 ? off + pos : -1;
 }
 
 struct CopyArgs {
     const void* x;
     const int32_t* topk_idx;
     const int32_t* cap;
-    const int32_t* expert_offset;
     int64_t S;
     int k, cpr, N, tile_shift;
     GateStats stats;
     int32_t* slot;
     void* send;
+    LayerOutputs lo;
     hipStream_t st;
 };
 
 template <int KK, int U>
 static void launch_route_copy(const CopyArgs& a) {
     const int64_t total = a.S * (int64_t)a.cpr;
-    const dim3 grid((unsigned)ceil_div(total, kCopyThreads * U)), block(kCopyThreads);
+    const dim3 grid((unsigned)ceil_div(total, kCopyThreads * U) + 1u), block(kCopyThreads);   // + workgroup 0
     const vec16* src = static_cast<const vec16*>(a.x);
     vec16* dst = static_cast<vec16*>(a.send);
     const int shift = pow2_shift(a.cpr);
     if (a.cpr % 64 == 0)
         route_copy_kernel<KK, U, true><<<grid, block, 0, a.st>>>(
-            src, a.topk_idx, a.stats.local_pos, a.stats.tile_pairs, a.cap, a.expert_offset, total, a.k, a.cpr, shift,
-            a.N, a.stats.n_blocks, a.stats.pitch, a.tile_shift, a.slot, dst);
+            src, a.topk_idx, a.stats.local_pos, a.stats.tile_pairs, a.cap, total, a.k, a.cpr, shift, a.N,
+            a.stats.n_blocks, a.stats.pitch, a.tile_shift, a.slot, dst, a.lo);
     else
         route_copy_kernel<KK, U, false><<<grid, block, 0, a.st>>>(
-            src, a.topk_idx, a.stats.local_pos, a.stats.tile_pairs, a.cap, a.expert_offset, total, a.k, a.cpr, shift,
-            a.N, a.stats.n_blocks, a.stats.pitch, a.tile_shift, a.slot, dst);
+            src, a.topk_idx, a.stats.local_pos, a.stats.tile_pairs, a.cap, total, a.k, a.cpr, shift, a.N,
+            a.stats.n_blocks, a.stats.pitch, a.tile_shift, a.slot, dst, a.lo);
 }
 
 }  // namespace tamoe
@@ -321,7 +413,7 @@ extern "C" int tamoe_gate_dispatch(const void* x, const void* w, int dtype, int6
     if ((rc = check_select_outputs(fn, S, topk_idx, topk_w, m, c_expert, c_device, ws, ws_bytes, lay)) != TAMOE_OK)
         return rc;
     const int cpr = d * elem_bytes(dtype) / 16;  // 16-byte chunks per row
-    if (S > 0 && ceil_div(S * (int64_t)cpr, kCopyThreads) > 0x7fffffff)
+    if (S > 0 && ceil_div(S * (int64_t)cpr, kCopyThreads) >= 0x7fffffff)   // one more workgroup is added
         return fail(TAMOE_UNSUPPORTED, "%s: x is too large for one launch", fn);
     hipStream_t st = static_cast<hipStream_t>(stream);
 
@@ -339,9 +431,8 @@ extern "C" int tamoe_gate_dispatch(const void* x, const void* w, int dtype, int6
     {
         TraceScope tr("route_expert_kernel", st);
         route_expert_kernel<<<dim3(N), dim3(kExpertThreads), 0, st>>>(
-            run.stats.m_part, run.stats.tile_pairs, run.stats.n_blocks, k * run.stats.n_blocks, run.stats.pitch, N, P, S,
-            penalty, scale, cap, m, c_expert, c_device, loss, kept_expert, expert_offset, send_count_dev,
-            run.stats.done);
+            run.stats.m_part, run.stats.tile_pairs, run.stats.n_blocks, k * run.stats.n_blocks, run.stats.pitch, S, cap,
+            m, c_expert, kept_expert);
     }
     if ((rc = check_launch(fn, "route_expert_kernel")) != TAMOE_OK) return rc;
 
@@ -349,7 +440,6 @@ extern "C" int tamoe_gate_dispatch(const void* x, const void* w, int dtype, int6
     a.x = x;
     a.topk_idx = topk_idx;
     a.cap = cap;
-    a.expert_offset = expert_offset;
     a.S = S;
     a.k = k;
     a.cpr = cpr;
@@ -358,6 +448,7 @@ extern "C" int tamoe_gate_dispatch(const void* x, const void* w, int dtype, int6
     a.stats = run.stats;
     a.slot = slot;
     a.send = send;
+    a.lo = LayerOutputs{m, c_expert, kept_expert, penalty, scale, P, c_device, loss, expert_offset, send_count_dev};
     a.st = st;
     // Slots in the scatter itself save a launch, but put two dependent table look-ups in front of every
     // wavefront's copy: that pays while the scatter is short (large configuration, 1 GiB of rows to
@@ -367,9 +458,9 @@ extern "C" int tamoe_gate_dispatch(const void* x, const void* w, int dtype, int6
         {
             TraceScope tr("route_slot_kernel", st);
             const int64_t pairs = S * k;
-            route_slot_kernel<<<dim3((unsigned)ceil_div(pairs, kCopyThreads)), dim3(kCopyThreads), 0, st>>>(
-                topk_idx, run.stats.local_pos, run.stats.tile_pairs, cap, expert_offset, pairs, k, N, run.stats.n_blocks,
-                run.stats.pitch, a.tile_shift, slot);
+            route_slot_kernel<<<dim3((unsigned)ceil_div(pairs, kCopyThreads) + 1u), dim3(kCopyThreads), 0, st>>>(
+                topk_idx, run.stats.local_pos, run.stats.tile_pairs, cap, pairs, k, N, run.stats.n_blocks, run.stats.pitch,
+                a.tile_shift, slot, a.lo);
         }
         if ((rc = check_launch(fn, "route_slot_kernel")) != TAMOE_OK) return rc;
         launch_dispatch_copy(x, slot, S, k, cpr, send, st);
