@@ -562,7 +562,6 @@ def main():
         "select_kernel": S * N * 4 + S * k * 8,
         "dispatch_copy_kernel": live_tokens * row + K * row + S * k * 8,
         "route_copy_kernel": live_tokens * row + K * row + S * k * 12,
-        "route_slot_kernel": S * k * 12,
         "combine_kernel": K * row + S * row + S * k * 8,
     }
     kernels = []

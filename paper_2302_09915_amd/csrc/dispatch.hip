@@ -264,7 +264,8 @@ static void launch_copy(const void* x, const int32_t* slot, int64_t S, int k, in
     }
 }
 
-void launch_dispatch_copy(const void* x, const int32_t* slot, int64_t S, int k, int cpr, void* send, hipStream_t st) {
+static void launch_dispatch_copy(const void* x, const int32_t* slot, int64_t S, int k, int cpr, void* send,
+                                 hipStream_t st) {
     TraceScope tr("dispatch_copy_kernel", st);
     if (k == 1)
         launch_copy<1, 2>(x, slot, S, k, cpr, send, st);

@@ -92,10 +92,6 @@ int check_select_outputs(const char* fn, int64_t S, int32_t* topk_idx, float* to
 constexpr int64_t kCacheResidentSendBytes = (int64_t)96 << 20;
 inline bool send_stays_in_cache(int64_t S, int k, int cpr) { return S * k * (int64_t)cpr * 16 <= kCacheResidentSendBytes; }
 
-// The scatter of tamoe_dispatch on a finished slot table: send[slot[t][j]] = x[t] for every slot >= 0.
-// cpr: 16-byte chunks per row.
-void launch_dispatch_copy(const void* x, const int32_t* slot, int64_t S, int k, int cpr, void* send, hipStream_t st);
-
 // log2(v) if v is a power of two, else -1.
 inline int pow2_shift(int v) {
     if (v <= 0 || (v & (v - 1)) != 0) return -1;

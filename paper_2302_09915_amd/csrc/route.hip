@@ -14,9 +14,8 @@
 //      thread derives the slots of its token on the way to moving its 16-byte chunk, and the thread
 //      with the row's first chunk writes them to slot[].  The first workgroup also writes what
 //      describes the layer as a whole: expert offsets, rows per destination device, the loss.
-//      When the send buffer is too large to stay in the last-level cache (96 MiB) the slots are written
-//      by route_slot_kernel (one thread per pair, same offsets, same first workgroup) and the rows are
-//      moved by the scatter of tamoe_dispatch: a fourth launch, but a shorter scatter.
+//      Rows are written with ordinary stores while the send buffer is small enough to stay in the
+//      last-level cache, with streaming stores beyond that (as in the scatter of tamoe_dispatch).
 #include "internal.h"
 
 namespace tamoe {
@@ -225,11 +224,11 @@ __global__ __launch_bounds__(kExpertThreads) void route_empty_kernel(int N, int 
 
 // The scatter with the slot assignment folded in.  Layout of the work as in dispatch_copy_kernel: one
 // 16-byte chunk per thread (two for k = 1), a wavefront inside one row when ROWU (its token's experts,
-// positions and table entries then go through the scalar unit).  Only launched for batches whose send
-// buffer fits the last-level cache, so the rows are written with ordinary stores.  Workgroup 0 writes
-// the layer's outputs and moves no rows: as part of a copying workgroup that tail would end after every
+// positions and table entries then go through the scalar unit).  STREAM: the rows are written with
+// streaming stores (send buffers too large to stay in the last-level cache).  Workgroup 0 writes the
+// layer's outputs and moves no rows: as part of a copying workgroup that tail would end after every
 // other workgroup of a short launch.
-template <int KK, int U, bool ROWU>
+template <int KK, int U, bool ROWU, bool STREAM>
 __global__ __launch_bounds__(kCopyThreads) void route_copy_kernel(
     const vec16* __restrict__ x, const int32_t* __restrict__ topk_idx, const int32_t* __restrict__ local_pos,
     const int32_t* __restrict__ tile_base, const int32_t* __restrict__ cap, int64_t total_chunks, int k_arg, int cpr,
@@ -320,37 +319,15 @@ __global__ __launch_bounds__(kCopyThreads) void route_copy_kernel(
         if (live[u]) {
 #pragma unroll
             for (int j = 0; j < KM; ++j)
-                if (sl[j] >= 0) send[(size_t)sl[j] * cpr + col[u]] = v[u];
+                if (sl[j] >= 0) {
+                    vec16* dst = send + (size_t)sl[j] * cpr + col[u];
+                    if (STREAM)
+                        __builtin_nontemporal_store(v[u], dst);
+                    else
+                        *dst = v[u];
+                }
         }
     }
-}
-
-// The slot of every pair by itself: one thread per pair.  For batches whose scatter is bound by
-// bandwidth, where the extra table lookups in front of every wavefront's copy would cost more than a
-// launch.  Workgroup 0 writes the layer's outputs instead.
-__global__ __launch_bounds__(kCopyThreads) void route_slot_kernel(
-    const int32_t* __restrict__ topk_idx, const int32_t* __restrict__ local_pos,
-    const int32_t* __restrict__ tile_base, const int32_t* __restrict__ cap, int64_t pairs, int k, int N, int n_blocks,
-    int pitch, int tile_shift, int32_t* __restrict__ slot, const LayerOutputs lo) {
-    if (blockIdx.x == 0) {
-        route_layer_outputs(lo.m, lo.c_expert, lo.kept_expert, lo.penalty, lo.loss_scale, N, lo.P, lo.c_device, lo.loss,
-                            lo.expert_offset, lo.send_count_dev);
-        return;
-    }
-    const KeptPair kp = load_kept(lo.kept_expert, N);
-    const int64_t p = (int64_t)(blockIdx.x - 1) * kCopyThreads + threadIdx.x;
-    const bool inside = p < pairs;
-    const int e = inside ? topk_idx[p] : -1;
-    const int32_t lp = inside ? local_pos[p] : 0;
-    const bool valid = e >= 0 && e < N;
-    const int ee = valid ? e : 0;                  // both table entries requested together, unconditionally
-    const int64_t t = inside ? p / k : 0;
-    const int j = inside ? (int)(p - t * k) : 0;
-    const int32_t q = tile_base[(size_t)ee * pitch + (size_t)j * n_blocks + (t >> tile_shift)] + lp;
-    const int32_t pos = (valid && q < cap[ee]) ? q : -1;
-    const WaveOffsets wo = wave_offsets(kp);
-    const int32_t off = offset_of<false>(wo, valid ? e : 0);
-    if (inside) slot[p] = pos >= 0 ? off + pos : -1;
 }
 
 struct CopyArgs {
@@ -373,14 +350,18 @@ static void launch_route_copy(const CopyArgs& a) {
     const vec16* src = static_cast<const vec16*>(a.x);
     vec16* dst = static_cast<vec16*>(a.send);
     const int shift = pow2_shift(a.cpr);
-    if (a.cpr % 64 == 0)
-        route_copy_kernel<KK, U, true><<<grid, block, 0, a.st>>>(
-            src, a.topk_idx, a.stats.local_pos, a.stats.tile_pairs, a.cap, total, a.k, a.cpr, shift, a.N,
-            a.stats.n_blocks, a.stats.pitch, a.tile_shift, a.slot, dst, a.lo);
-    else
-        route_copy_kernel<KK, U, false><<<grid, block, 0, a.st>>>(
-            src, a.topk_idx, a.stats.local_pos, a.stats.tile_pairs, a.cap, total, a.k, a.cpr, shift, a.N,
-            a.stats.n_blocks, a.stats.pitch, a.tile_shift, a.slot, dst, a.lo);
+    const bool rowu = a.cpr % 64 == 0;
+    const bool stream = !send_stays_in_cache(a.S, a.k, a.cpr);
+#define TAMOE_ROUTE_COPY(RU, ST)                                                                                   \
+    route_copy_kernel<KK, U, RU, ST><<<grid, block, 0, a.st>>>(                                                    \
+        src, a.topk_idx, a.stats.local_pos, a.stats.tile_pairs, a.cap, total, a.k, a.cpr, shift, a.N,             \
+        a.stats.n_blocks, a.stats.pitch, a.tile_shift, a.slot, dst, a.lo)
+    if (rowu) {
+        if (stream) TAMOE_ROUTE_COPY(true, true); else TAMOE_ROUTE_COPY(true, false);
+    } else {
+        if (stream) TAMOE_ROUTE_COPY(false, true); else TAMOE_ROUTE_COPY(false, false);
+    }
+#undef TAMOE_ROUTE_COPY
 }
 
 }  // namespace tamoe
@@ -450,22 +431,6 @@ extern "C" int tamoe_gate_dispatch(const void* x, const void* w, int dtype, int6
     a.send = send;
     a.lo = LayerOutputs{m, c_expert, kept_expert, penalty, scale, P, c_device, loss, expert_offset, send_count_dev};
     a.st = st;
-    // Slots in the scatter itself save a launch, but put two dependent table look-ups in front of every
-    // wavefront's copy: that pays while the scatter is short (large configuration, 1 GiB of rows to
-    // write: 270 us against 257 + 4 us for the two kernels; GPT-MoE layer, 64 MiB: a step of 61 against
-    // 63 us).  The line is drawn where the send buffer stops fitting the last-level cache.
-    if (!send_stays_in_cache(S, k, cpr)) {
-        {
-            TraceScope tr("route_slot_kernel", st);
-            const int64_t pairs = S * k;
-            route_slot_kernel<<<dim3((unsigned)ceil_div(pairs, kCopyThreads) + 1u), dim3(kCopyThreads), 0, st>>>(
-                topk_idx, run.stats.local_pos, run.stats.tile_pairs, cap, pairs, k, N, run.stats.n_blocks, run.stats.pitch,
-                a.tile_shift, slot, a.lo);
-        }
-        if ((rc = check_launch(fn, "route_slot_kernel")) != TAMOE_OK) return rc;
-        launch_dispatch_copy(x, slot, S, k, cpr, send, st);
-        return check_launch(fn, "dispatch_copy_kernel");
-    }
     {
         TraceScope tr("route_copy_kernel", st);
         if (k == 1)
