@@ -317,6 +317,8 @@ def test_eight_wavefront_gate_shapes(T, oracle, dtype, d, N, P, k):
     (W.BF16, 2500, 264, 96, 8, 2, 2.0),    # several count tiles, ragged end
     (W.BF16, 70000, 16, 32, 4, 1, 1.1),    # many tokens, tiny rows
     (W.BF16, 70001, 1024, 96, 8, 3, 0.9),  # 410 MiB of rows to send: the fused call's scatter writes them with streaming stores
+    (W.BF16, 60000, 1000, 64, 8, 2, 1.0),  # the same with rows that are no multiple of 1 KiB (a wavefront spans tokens)
+    (W.F16, 70001, 1000, 40, 8, 1, 1.5),   # and with one choice (two chunks per thread)
     (W.F16, 33, 72, 5, 5, 2, 1.0),         # half precision: ragged tile, K tail, odd N
     (W.F16, 2500, 264, 96, 8, 2, 2.0),
     (W.F16, 1000, 64, 128, 64, 8, 1.0),
