@@ -12,6 +12,7 @@ from __future__ import annotations
 
 import ctypes
 import os
+import threading
 from typing import Dict, Optional
 
 import numpy as np
@@ -54,9 +55,62 @@ _lib = None
 dbl_t = ctypes.c_double
 
 
+_bind_state = threading.local()
+
+
+class _Recorder:
+    """Stands in for the library while bind() runs a binding function: notes the entry point and its
+    marshalled arguments instead of calling it."""
+
+    def __init__(self):
+        self.calls = []
+
+    def __getattr__(self, name):
+        def note(*args):
+            self.calls.append((name, args))
+            return OK
+        return note
+
+
+class BoundCall:
+    """One device entry point with its arguments checked and marshalled once.  For loops that call
+    the library on the same buffers again and again: converting twenty tensors costs more host time
+    per call than a small launch takes on the device.  The tensors are kept alive; the stream is the
+    one that was current (or given) when bind() ran, so a bound call must not be used under a stream
+    capture that began afterwards."""
+
+    __slots__ = ("_fn", "_args", "_keep")
+
+    def __init__(self, fn, args, keep):
+        self._fn, self._args, self._keep = fn, args, keep
+
+    def __call__(self) -> None:
+        status = self._fn(*self._args)
+        if status != OK:
+            raise TamoeError(status, lib().tamoe_last_error().decode())
+
+
+def bind(entry, *args, **kwargs) -> BoundCall:
+    """bind(tamoe_combine, recv, K, slot, topk_w, y) -> a callable that makes exactly that call."""
+    real = lib()
+    rec = _Recorder()
+    _bind_state.recorder = rec
+    try:
+        entry(*args, **kwargs)
+    finally:
+        _bind_state.recorder = None
+    if len(rec.calls) != 1:
+        raise TamoeError(INVALID_ARG, "bind() takes one of the tamoe_* device entry points")
+    name, cargs = rec.calls[0]
+    return BoundCall(getattr(real, name), cargs, (args, kwargs))
+
+
 def lib() -> ctypes.CDLL:
     """The loaded library.  Raises if it has not been built (python -m paper_2302_09915_amd.build)."""
     global _lib
+    rec = getattr(_bind_state, "recorder", None)
+    if rec is not None:
+        return rec
     if _lib is not None:
         return _lib
     if not os.path.exists(LIB_PATH):

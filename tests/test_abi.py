@@ -276,3 +276,18 @@ def test_binding_has_no_cpu_fallback(T, monkeypatch):
         pkg.lib()
     src = open(os.path.join(ROOT, "paper_2302_09915_amd", "__init__.py")).read()
     assert "import oracle" not in src and "from oracle" not in src
+
+
+def test_bind_notes_one_call_and_restores_the_library(T):
+    import torch
+
+    """bind() runs a binding function against a stand-in that only notes the call; whatever happens
+    inside, the real library is back afterwards."""
+    with pytest.raises(T.TamoeError):
+        T.bind(lambda: None)                                   # no entry point called
+    with pytest.raises(T.TamoeError):
+        T.bind(T.tamoe_combine, None, 0, torch.zeros((4, 2), dtype=torch.int32), None, torch.zeros((4, 8)))
+    assert T.lib().tamoe_version() == T.tamoe_version() > 0    # not the stand-in
+    call = T.bind(T.tamoe_version)                              # a call whose result is not a status of 0
+    with pytest.raises(T.TamoeError):
+        call()

@@ -543,6 +543,35 @@ def test_runs_are_bitwise_repeatable_and_logits_are_optional(T):
     assert torch.equal(a["send_t"][: a["K"]].view(torch.int16), b["send_t"][: b["K"]].view(torch.int16))
 
 
+def test_bound_calls_repeat_the_call_they_were_made_from(T):
+    """T.bind: arguments marshalled once, same launches, same bits."""
+    wl = W.WORKLOADS["small"]
+    inp = W.make_inputs(wl)
+    beta, level = W.topology(wl)
+    _, pen, cap = T.tamoe_topo_pattern(beta, level, wl.P, wl.N, 0, wl.k, wl.S, wl.capacity_factor, 0)
+    x, w = to_dev(inp["x"], wl.dtype), to_dev(inp["w"], wl.dtype)
+    pen_d, cap_d = torch.from_numpy(pen).cuda(), torch.from_numpy(cap).cuda()
+    a = T.gate_dispatch(x, w, wl.P, wl.k, pen_d, cap_d, want_logits=False)
+    ya = T.combine(a["send"], wl.S * wl.k, a["slot"], a["topk_w"])
+    b = {key: (torch.zeros_like(v) if v is not None else None) for key, v in a.items()}
+    yb = torch.zeros_like(ya)
+    ws = T.workspace(wl.S, wl.d, wl.N, wl.P, wl.k, wl.dtype)
+    calls = [T.bind(T.tamoe_gate_dispatch, x, w, wl.P, wl.k, pen_d, cap_d, None, b["topk_idx"], b["topk_w"], b["m"],
+                    b["c_expert"], b["c_device"], b["loss"], b["send"], b["slot"], b["kept_expert"],
+                    b["expert_offset"], b["send_count_dev"], ws),
+             T.bind(T.tamoe_combine, b["send"], wl.S * wl.k, b["slot"], b["topk_w"], yb)]
+    for _ in range(2):
+        for c in calls:
+            c()
+    torch.cuda.synchronize()
+    K = int(a["expert_offset"][-1].item())
+    for key in ("topk_idx", "topk_w", "m", "c_expert", "c_device", "loss", "slot", "kept_expert", "expert_offset",
+                "send_count_dev"):
+        assert torch.equal(a[key], b[key]), key
+    assert torch.equal(a["send"][:K].view(torch.int16), b["send"][:K].view(torch.int16))
+    assert torch.equal(ya.view(torch.int16), yb.view(torch.int16))
+
+
 def test_aux_loss_closed_forms_on_device(T):
     """Uniform routing: l_topo = k/E for any penalty that sums to one; l_aux = k/N."""
     N, P, k, S = 64, 32, 2, 4096
